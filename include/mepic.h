@@ -1,0 +1,219 @@
+/*
+ * mepic.h — C-ABI boundary of the MI355X (gfx950) implementation of the hot path of MEPIC's
+ * position-independent KV caching: paged-KV attention with rotary embedding fused into the kernel,
+ * plus the host-side page pool / chunk-to-page aligner that produces the block tables.
+ *
+ * Paper passages each call follows are cited per declaration (section / algorithm / figure only).
+ *
+ * Conventions that hold for every call:
+ *   - returns a mepic_status (0 = ok, negative = error); nothing throws or aborts across the ABI;
+ *   - the caller owns every buffer. "device" pointers are HIP device memory reachable from the
+ *     current device; "host" pointers are ordinary host memory. The library never allocates or frees
+ *     device memory; the pool owns only its own host metadata;
+ *   - attention calls are asynchronous on the given HIP stream; the params struct is read on the host
+ *     during the call and may be freed as soon as the call returns;
+ *   - outputs are undefined after an error;
+ *   - the pool is not thread-safe (one scheduler thread, as in the paper's scheduling path, §3.2).
+ */
+#ifndef MEPIC_H
+#define MEPIC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MEPIC_OK = 0,
+  MEPIC_ERR_INVALID = -1,     /* null pointer, zero-length segment, inconsistent shapes, key/length clash */
+  MEPIC_ERR_NOMEM = -2,       /* Alg. 1 "Reject": free + evictable pages cannot cover the demand          */
+  MEPIC_ERR_CAPACITY = -3,    /* a caller-supplied output buffer or workspace is too small                */
+  MEPIC_ERR_UNSUPPORTED = -4, /* shape / dtype combination no kernel is built for                         */
+  MEPIC_ERR_LAUNCH = -5       /* the HIP runtime reported an error at launch                              */
+} mepic_status;
+
+/* Static, human-readable text for a status code (never NULL). */
+const char* mepic_strerror(int status);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int mepic_version(void);
+
+/* ------------------------------------------------------------------------------------------------
+ * Host-side page pool and chunk-to-page aligner (metadata only; §3.2, Alg. 1).
+ *
+ * The pool tracks `num_pages` physical KV pages of `page_size` token slots each. One pool serves
+ * request-private pages and shared chunk pages alike (§3.2.3 "shared paged-KV block pool").
+ *
+ * Allocation policy is deterministic so block tables are reproducible bit for bit:
+ *   - the lowest-numbered free page is handed out first;
+ *   - segments are processed left to right; for a chunk occurrence the private first block is
+ *     allocated before the chunk's shared pages.
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct mepic_pool mepic_pool; /* opaque */
+
+enum { MEPIC_SEG_PROMPT = 0, MEPIC_SEG_CHUNK = 1 };
+
+/* One segment of a request (§3.2.1): request-specific prompt text, or an immutable reusable chunk. */
+typedef struct {
+  uint32_t kind;      /* MEPIC_SEG_PROMPT or MEPIC_SEG_CHUNK                                        */
+  uint32_t n_tokens;  /* > 0                                                                        */
+  uint64_t chunk_key; /* identity of the chunk's padded token sequence (§3.2.3); ignored for prompts.
+                         Two segments with equal key must have equal n_tokens.                      */
+} mepic_segment;
+
+/* Per-block provenance written by mepic_align_request. */
+enum { MEPIC_BLOCK_PRIVATE = 0, MEPIC_BLOCK_SHARED_HIT = 1, MEPIC_BLOCK_SHARED_NEW = 2 };
+
+typedef struct {
+  uint32_t n_blocks;     /* logical blocks of the aligned request (= block-table entries written)   */
+  uint32_t n_private;    /* request-private blocks (prompt blocks + the first block of every chunk) */
+  uint32_t n_shared_hit; /* shared blocks whose chunk was already resident                          */
+  uint32_t n_shared_new; /* shared blocks allocated for a chunk seen for the first time             */
+  uint32_t n_pad_slots;  /* pad slots inserted (leading pads of chunks + trailing pads of prompts)   */
+  uint32_t kv_len;       /* length of the padded sequence T_align, including extra_tail_tokens      */
+  uint32_t n_evicted_chunks; /* zero-reference chunks evicted to admit this request                 */
+} mepic_align_info;
+
+typedef struct {
+  uint64_t pages_total;
+  uint64_t pages_free;
+  uint64_t pages_in_use_unique;      /* pages currently allocated (private + resident shared)       */
+  uint64_t pages_logical_duplicated; /* sum of n_blocks over live requests: what a layout in which
+                                        every request owns all of its blocks would occupy           */
+  uint64_t chunks_resident;          /* chunks whose shared pages are in the pool                   */
+  uint64_t chunks_zero_ref;          /* resident chunks no live request references (evictable)      */
+  uint64_t requests_live;
+  uint64_t peak_pages_in_use_unique; /* high-water marks since creation                              */
+  uint64_t peak_pages_logical_duplicated;
+} mepic_pool_stats;
+
+/* Create a pool of `num_pages` pages with `page_size` slots (1..32) each. *out receives the pool. */
+int mepic_pool_create(uint32_t num_pages, uint32_t page_size, mepic_pool** out);
+void mepic_pool_destroy(mepic_pool* pool);
+
+/*
+ * Align one request to pages and assign its blocks (Alg. 1: segmentation and canonicalisation,
+ * residency resolution, admission check, block allocation; padding rule of §3.2.1; first-block rule
+ * of §3.2.3 / §3.3.1).
+ *
+ *   segs[n_segs]       host, the request's segments in order.
+ *   extra_tail_tokens  tokens appended after the last segment in request-private pages (1 for the
+ *                      token being decoded). They continue in a final prompt segment's partial block.
+ *   block_table_out    host int32[capacity]: physical page of each logical block.
+ *   block_kind_out     host uint8[capacity] or NULL: MEPIC_BLOCK_* of each block.
+ *   block_valid_out    host uint32[capacity] or NULL: bit s set iff slot s of the block holds a real
+ *                      token (pad slots and the unused tail of the last block are 0).
+ *   block_pos_out      host int32[capacity] or NULL: position of slot 0 of the block when pad slots
+ *                      are NOT counted as positions (may be negative for a leading pad at the start).
+ *   request_handle_out host, handle to pass to mepic_release_request.
+ *
+ * Layout rule: a prompt segment of n tokens takes ceil(n/P) private blocks with trailing pad, except
+ * that the last segment of the request, if a prompt, keeps a partially filled last block; a chunk of n
+ * tokens takes ceil(n/P) blocks with ceil(n/P)*P - n leading pad slots, block 0 private and blocks
+ * 1.. shared by key. A chunk of at most P tokens owns no shared page and is not registered.
+ *
+ * Admission: the demand is the private blocks plus the shared blocks of chunks not resident. If it
+ * exceeds the free pages plus the pages of zero-reference chunks this request does not itself use,
+ * MEPIC_ERR_NOMEM is returned and the pool is unchanged. Otherwise zero-reference chunks are evicted
+ * whole, least recently used first, only as far as needed (§3.2.3 eviction policy).
+ *
+ * Errors: MEPIC_ERR_INVALID (null pointers, zero-length segment, bad kind, key reused with another
+ * length), MEPIC_ERR_CAPACITY (capacity < n_blocks; pool unchanged), MEPIC_ERR_NOMEM.
+ */
+int mepic_align_request(mepic_pool* pool, const mepic_segment* segs, uint32_t n_segs,
+                        uint32_t extra_tail_tokens, int32_t* block_table_out, uint32_t capacity,
+                        uint8_t* block_kind_out, uint32_t* block_valid_out, int32_t* block_pos_out,
+                        uint64_t* request_handle_out, mepic_align_info* info_out);
+
+/* Drop a request: its private pages return to the free list, each chunk occurrence gives back one
+ * reference; chunks that reach zero stay resident until evicted. MEPIC_ERR_INVALID for an unknown
+ * handle. */
+int mepic_release_request(mepic_pool* pool, uint64_t request_handle);
+
+int mepic_pool_get_stats(const mepic_pool* pool, mepic_pool_stats* out);
+
+/* Is the chunk resident, and with how many references? Returns MEPIC_OK and writes 0/1 to
+ * *resident_out (and the count to *refcount_out if not NULL). (Chunk Matcher lookup, §3.2.2.) */
+int mepic_pool_lookup_chunk(const mepic_pool* pool, uint64_t chunk_key, int* resident_out,
+                            uint32_t* refcount_out);
+
+/* ------------------------------------------------------------------------------------------------
+ * Fused-RoPE paged attention (§3.3.3): K is stored WITHOUT positional encoding; the kernels gather
+ * pages through the block table, rotate K and Q at the request's own absolute positions on chip and
+ * run online-softmax attention. V is never rotated.
+ *
+ * Rotary convention (the paper prints no formula): frequency f_i = theta^(-2i/D), i in [0, D/2);
+ * angle a = position * f_i; pair (x[i], x[i+D/2]) -> (x[i] cos a - x[i+D/2] sin a,
+ * x[i+D/2] cos a + x[i] sin a). With MEPIC_FLAG_ROPE_INTERLEAVED the pair is (x[2i], x[2i+1]).
+ *
+ * Page layout (a choice of this library; the paper fixes none). Let E = bytes per KV element and
+ * X = 16 / E elements (one 16-byte granule: 4 fp32, 8 bf16, 16 fp8). For page p and KV head h:
+ *   K: element (slot s, dim d) at  k_pages[(((p*Hkv + h)*(D/X) + d/X)*P + s)*X + d%X]
+ *      i.e. [num_pages][Hkv][D/X][P][X] — for a fixed granule the P slots are contiguous;
+ *   V: element (slot s, dim d) at  v_pages[((p*Hkv + h)*D + d)*P + s]
+ *      i.e. [num_pages][Hkv][D][P] — for a fixed dim the P slots are contiguous.
+ * Both make every matrix-core operand a single aligned 16-byte load straight from the page.
+ *
+ * Logical slot n of request b lives in block j = n / P, slot s = n % P, page block_tables[b][j]; its
+ * position is block_positions[b][j] + s, or n when block_positions is NULL (the index in T_align).
+ * Slot n takes part iff n < kv_lens[b], its bit in block_valid_mask is set (when given) and, for
+ * prefill, position(n) <= position of the query token (causal by absolute position).
+ * Query head h reads KV head h / (Hq / Hkv). If no slot takes part the output row is all zeros.
+ * ---------------------------------------------------------------------------------------------- */
+typedef enum { MEPIC_F32 = 0, MEPIC_BF16 = 1, MEPIC_F8E4M3 = 2 } mepic_dtype;
+
+enum {
+  MEPIC_FLAG_ROPE_INTERLEAVED = 1u, /* pair (x[2i], x[2i+1]) instead of (x[i], x[i+D/2])              */
+  MEPIC_FLAG_FORCE_GENERAL = 2u     /* run the general kernel even where a matrix-core kernel exists
+                                       (for tests: both must agree with the oracle)                  */
+};
+
+typedef struct {
+  const void* q;                    /* device [n_q_tokens][Hq][D], q_dtype, UN-rotated                */
+  void* out;                        /* device [n_q_tokens][Hq][D], q_dtype                            */
+  const void* k_pages;              /* device, K page layout above, kv_dtype, UN-rotated              */
+  const void* v_pages;              /* device, V page layout above, kv_dtype                          */
+  const float* k_scales;            /* device [num_pages] fp32; required iff kv_dtype == F8E4M3:      */
+  const float* v_scales;            /*   stored value = e4m3fn code * scale of its page               */
+  const int32_t* block_tables;      /* device [B][max_blocks] physical page ids in [0, num_pages)     */
+  const int32_t* kv_lens;           /* device [B] valid KV slots per request (<= max_blocks * P)      */
+  const int32_t* q_positions;       /* device [n_q_tokens] absolute position of each query token      */
+  const int32_t* cu_q_lens;         /* device [B+1] prefix sums of query tokens per request; prefill
+                                       only. Decode has one query token per request: n_q_tokens == B  */
+  const int32_t* block_positions;   /* device [B][max_blocks] or NULL                                 */
+  const uint32_t* block_valid_mask; /* device [B][max_blocks] or NULL                                 */
+  int32_t B, n_q_tokens, Hq, Hkv, D, P, max_blocks, num_pages;
+  int32_t max_kv_len;               /* host-known upper bound on kv_lens[] (sizes the split-K grid);
+                                       <= 0 means max_blocks * P                                      */
+  int32_t max_q_len;                /* prefill: host-known upper bound on query tokens per request;
+                                       <= 0 means n_q_tokens                                          */
+  int32_t q_dtype, kv_dtype;        /* (F32,F32) | (BF16,BF16) | (BF16,F8E4M3)                        */
+  float rope_theta;
+  float sm_scale;                   /* <= 0 means 1/sqrt(D)                                           */
+  uint32_t flags;                   /* MEPIC_FLAG_*                                                   */
+  void* workspace;                  /* device scratch for split-K partials, 256-byte aligned          */
+  size_t workspace_bytes;
+} mepic_attn_params;
+
+/* Bytes of workspace mepic_attn_decode / mepic_attn_prefill need for these shapes (only the shape,
+ * dtype and max_* fields are read). */
+int mepic_attn_workspace_size(const mepic_attn_params* params, int is_prefill, size_t* bytes_out);
+
+/* Decode: one query token per request attends to all of the request's valid slots (§3.3.3). */
+int mepic_attn_decode(const mepic_attn_params* params, void* hip_stream);
+
+/* Prefill of question tokens: the tokens cu_q_lens[b]..cu_q_lens[b+1] of request b attend causally,
+ * by absolute position, to the request's slots; their own K/V are already committed to the request's
+ * private pages (§3.3.2 precedes §3.3.3). */
+int mepic_attn_prefill(const mepic_attn_params* params, void* hip_stream);
+
+/* Name of the kernel variant the last attention call on this thread dispatched to (static string;
+ * "" before any call). For tests and reports. */
+const char* mepic_last_kernel(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MEPIC_H */

@@ -1,0 +1,141 @@
+// C-ABI entry points of the attention half of the library: argument checks, the split-K plan, the
+// rotary frequency table, and dispatch to the kernels. No device memory is allocated here.
+#include <cmath>
+#include <cstring>
+
+#include "attn_common.h"
+
+namespace mepic {
+namespace {
+
+thread_local const char* g_last_kernel = "";
+
+enum Kernel { K_GENERAL = 0, K_DECODE_MFMA_BF16 = 1, K_DECODE_MFMA_F8 = 2, K_PREFILL_MFMA_BF16 = 3 };
+
+struct Plan {
+  Kernel kernel;
+  int n_splits, blocks_per_split;
+  size_t workspace_bytes;
+};
+
+int check_shapes(const mepic_attn_params* p, bool prefill) {
+  if (!p) return MEPIC_ERR_INVALID;
+  if (p->B < 0 || p->n_q_tokens < 0 || p->Hq <= 0 || p->Hkv <= 0 || p->max_blocks < 0 || p->num_pages < 0)
+    return MEPIC_ERR_INVALID;
+  if (p->Hq % p->Hkv) return MEPIC_ERR_INVALID;
+  if (!prefill && p->n_q_tokens != p->B) return MEPIC_ERR_INVALID;
+  const bool combo = (p->q_dtype == MEPIC_F32 && p->kv_dtype == MEPIC_F32) ||
+                     (p->q_dtype == MEPIC_BF16 && p->kv_dtype == MEPIC_BF16) ||
+                     (p->q_dtype == MEPIC_BF16 && p->kv_dtype == MEPIC_F8E4M3);
+  if (!combo) return MEPIC_ERR_UNSUPPORTED;
+  if (p->D != 64 && p->D != 128) return MEPIC_ERR_UNSUPPORTED;
+  if (p->P != 16 && p->P != 32) return MEPIC_ERR_UNSUPPORTED;
+  if (p->Hq / p->Hkv > kMaxG) return MEPIC_ERR_UNSUPPORTED;
+  if (p->Hkv > 65535) return MEPIC_ERR_UNSUPPORTED;
+  return MEPIC_OK;
+}
+
+Plan make_plan(const mepic_attn_params* p, bool prefill) {
+  Plan pl{};
+  const int G = p->Hq / p->Hkv;
+  int max_kv = p->max_kv_len > 0 ? p->max_kv_len : p->max_blocks * p->P;
+  if (max_kv > p->max_blocks * p->P) max_kv = p->max_blocks * p->P;
+  const int n_blocks = (max_kv + p->P - 1) / p->P;
+  const bool plain = !p->block_positions && !p->block_valid_mask &&
+                     !(p->flags & (MEPIC_FLAG_ROPE_INTERLEAVED | MEPIC_FLAG_FORCE_GENERAL));
+  (void)G;
+  (void)plain;
+  pl.kernel = K_GENERAL;
+
+  // General path: one workgroup per (query token, KV head, split); a split is a whole number of
+  // 256-slot tiles. Enough splits to put ~8 workgroups on each of the 256 compute units.
+  const int tile_blocks = 256 / p->P;
+  const long rows = (long)p->n_q_tokens * p->Hkv;
+  int want = rows > 0 ? (int)((2048 + rows - 1) / rows) : 1;
+  const int max_splits = (n_blocks + tile_blocks - 1) / tile_blocks;
+  if (want > max_splits) want = max_splits;
+  if (want > 1024) want = 1024;
+  if (want < 1) want = 1;
+  int bps = (n_blocks + want - 1) / want;
+  bps = (bps + tile_blocks - 1) / tile_blocks * tile_blocks;
+  if (bps < tile_blocks) bps = tile_blocks;
+  pl.blocks_per_split = bps;
+  pl.n_splits = n_blocks > 0 ? (n_blocks + bps - 1) / bps : 1;
+  pl.workspace_bytes = (size_t)p->n_q_tokens * p->Hq * pl.n_splits * (p->D + 2) * sizeof(float);
+  return pl;
+}
+
+int run(const mepic_attn_params* p, void* hip_stream, bool prefill) {
+  const int rc = check_shapes(p, prefill);
+  if (rc != MEPIC_OK) return rc;
+  if (p->n_q_tokens == 0) return MEPIC_OK;
+  if (!p->q || !p->out || !p->k_pages || !p->v_pages || !p->block_tables || !p->kv_lens || !p->q_positions)
+    return MEPIC_ERR_INVALID;
+  if (prefill && !p->cu_q_lens) return MEPIC_ERR_INVALID;
+  if (p->kv_dtype == MEPIC_F8E4M3 && (!p->k_scales || !p->v_scales)) return MEPIC_ERR_INVALID;
+  if (!(p->rope_theta > 0.f)) return MEPIC_ERR_INVALID;
+
+  const Plan pl = make_plan(p, prefill);
+  if (pl.workspace_bytes && (!p->workspace || p->workspace_bytes < pl.workspace_bytes)) return MEPIC_ERR_CAPACITY;
+  if (reinterpret_cast<uintptr_t>(p->workspace) & 255u) return MEPIC_ERR_INVALID;
+
+  AttnArgs a{};
+  a.q = p->q; a.out = p->out; a.k_pages = p->k_pages; a.v_pages = p->v_pages;
+  a.k_scales = p->k_scales; a.v_scales = p->v_scales;
+  a.block_tables = p->block_tables; a.kv_lens = p->kv_lens; a.q_positions = p->q_positions;
+  a.cu_q_lens = prefill ? p->cu_q_lens : nullptr;
+  a.block_positions = p->block_positions; a.block_valid_mask = p->block_valid_mask;
+  a.B = p->B; a.n_q = p->n_q_tokens; a.Hq = p->Hq; a.Hkv = p->Hkv; a.D = p->D; a.P = p->P;
+  a.max_blocks = p->max_blocks; a.num_pages = p->num_pages; a.G = p->Hq / p->Hkv;
+  a.q_dtype = p->q_dtype; a.kv_dtype = p->kv_dtype;
+  a.interleaved = (p->flags & MEPIC_FLAG_ROPE_INTERLEAVED) ? 1 : 0;
+  a.causal = prefill ? 1 : 0;
+  a.n_splits = pl.n_splits; a.blocks_per_split = pl.blocks_per_split;
+  const double sm = p->sm_scale > 0.f ? (double)p->sm_scale : 1.0 / std::sqrt((double)p->D);
+  a.qk_scale_log2 = (float)(sm * 1.4426950408889634);
+  // frequencies in turns per position, f_i / (2 pi), as a two-float sum
+  for (int i = 0; i < p->D / 2; ++i) {
+    const double f = std::pow((double)p->rope_theta, -2.0 * i / (double)p->D) / 6.283185307179586476925;
+    a.freq_hi[i] = (float)f;
+    a.freq_lo[i] = (float)(f - (double)a.freq_hi[i]);
+  }
+  float* ws = reinterpret_cast<float*>(p->workspace);
+  a.part_o = ws;
+  a.part_ml = ws + (size_t)a.n_q * a.Hq * a.n_splits * a.D;
+
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  hipError_t e = hipSuccess;
+  switch (pl.kernel) {
+    default:
+      g_last_kernel = "general";
+      e = launch_general(a, s);
+      if (e == hipSuccess) e = launch_combine(a, s);
+      break;
+  }
+  return e == hipSuccess ? MEPIC_OK : MEPIC_ERR_LAUNCH;
+}
+
+}  // namespace
+}  // namespace mepic
+
+extern "C" {
+
+int mepic_attn_workspace_size(const mepic_attn_params* params, int is_prefill, size_t* bytes_out) {
+  if (!bytes_out) return MEPIC_ERR_INVALID;
+  const int rc = mepic::check_shapes(params, is_prefill != 0);
+  if (rc != MEPIC_OK) return rc;
+  *bytes_out = mepic::make_plan(params, is_prefill != 0).workspace_bytes;
+  return MEPIC_OK;
+}
+
+int mepic_attn_decode(const mepic_attn_params* params, void* hip_stream) {
+  return mepic::run(params, hip_stream, false);
+}
+
+int mepic_attn_prefill(const mepic_attn_params* params, void* hip_stream) {
+  return mepic::run(params, hip_stream, true);
+}
+
+const char* mepic_last_kernel(void) { return mepic::g_last_kernel; }
+
+}  // extern "C"

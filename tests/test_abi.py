@@ -1,0 +1,71 @@
+"""The C-ABI library loads, exports every symbol include/mepic.h declares, and rejects bad arguments on
+the host before anything is launched (so these run without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "mepic.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mepic_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(mepic):
+    lib = mepic.load()
+    names = declared_symbols()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in mepic.h but not exported"
+    assert sorted(mepic.EXPORTS) == names, "the binding's list and the header disagree"
+    assert mepic.version() >= 100
+    assert mepic.strerror(0) == "ok" and "reject" in mepic.strerror(mepic.ERR_NOMEM).lower()
+    assert mepic.last_kernel() == "" or isinstance(mepic.last_kernel(), str)
+
+
+def test_product_does_not_import_the_oracle():
+    """The product path may not route through the oracle or any CPU fallback."""
+    pkg = os.path.join(ROOT, "paper_2512_16822_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".cpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.replace("not import the oracle", ""), f"{f} mentions the oracle"
+
+
+def params(mepic, **over):
+    p = mepic.AttnParams()
+    base = dict(B=2, n_q_tokens=2, Hq=8, Hkv=2, D=128, P=16, max_blocks=4, num_pages=8, q_dtype=mepic.BF16,
+                kv_dtype=mepic.BF16, rope_theta=1e4)
+    base.update(over)
+    for k, v in base.items():
+        setattr(p, k, v)
+    return p
+
+
+def test_workspace_size_and_shape_errors(mepic):
+    n = mepic.attn_workspace_size(params(mepic), False)
+    assert n > 0 and n % 4 == 0
+    for bad, status in ((dict(D=96), mepic.ERR_UNSUPPORTED), (dict(P=8), mepic.ERR_UNSUPPORTED),
+                        (dict(Hq=7), mepic.ERR_INVALID), (dict(q_dtype=mepic.F32), mepic.ERR_UNSUPPORTED),
+                        (dict(kv_dtype=mepic.F32), mepic.ERR_UNSUPPORTED), (dict(Hq=68, Hkv=2), mepic.ERR_UNSUPPORTED),
+                        (dict(n_q_tokens=3), mepic.ERR_INVALID)):
+        with pytest.raises(mepic.MepicError) as e:
+            mepic.attn_workspace_size(params(mepic, **bad), False)
+        assert e.value.status == status, bad
+    # prefill may have more query tokens than requests
+    assert mepic.attn_workspace_size(params(mepic, n_q_tokens=40), True) > 0
+
+
+def test_null_pointers_are_rejected_before_any_launch(mepic):
+    lib = mepic.load()
+    p = params(mepic)
+    assert lib.mepic_attn_decode(ctypes.byref(p), None) == mepic.ERR_INVALID       # q, out, pages ... are NULL
+    assert lib.mepic_attn_decode(None, None) == mepic.ERR_INVALID
+    assert lib.mepic_attn_workspace_size(ctypes.byref(p), 0, None) == mepic.ERR_INVALID
+    assert lib.mepic_pool_create(4, 16, None) == mepic.ERR_INVALID
+    assert lib.mepic_pool_get_stats(None, None) == mepic.ERR_INVALID

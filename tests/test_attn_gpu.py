@@ -1,0 +1,198 @@
+"""GPU parity: the library's attention (through the C-ABI) against the fp64 oracle, element by element,
+on the same seeded inputs. Block tables come from the oracle's aligner and are also checked against
+the library's aligner. Tolerances: 1e-4 max-abs for fp32 storage, 2e-2 for bf16 and bf16+fp8."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from harness import DeviceCase, align_with_library, align_with_oracle, oracle_out
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2, "f8e4m3": 2e-2}
+
+
+def build_case(M, st, **kw):
+    aligned, _ = align_with_oracle(st)
+    lib_aligned, _ = align_with_library(M, st)
+    for a, b in zip(aligned, lib_aligned):                      # page-table parity is bit-exact
+        assert b["block_table"].tolist() == a["block_table"] and b["info"] == a["info"]
+    return W.assemble(st, aligned, **kw)
+
+
+def check(M, oracle_attn, case, flags=0, rows=None, expect_kernel=None, **okw):
+    dc = DeviceCase(M, case, flags=flags | (M.FLAG_ROPE_INTERLEAVED if okw.get("interleaved") else 0),
+                    sm_scale=okw.get("sm_scale", 0.0))
+    got = dc.run()
+    if expect_kernel is not None:
+        assert M.last_kernel() == expect_kernel, M.last_kernel()
+    want = oracle_out(oracle_attn, case, rows=rows, **okw)
+    if rows is not None:
+        got = np.stack([got[t, h] for t, h in rows])
+    assert got.shape == want.shape
+    assert np.isfinite(got).all(), "non-finite output (a poisoned slot or page leaked in)"
+    err = np.abs(got - want).max() if got.size else 0.0
+    assert err <= TOL[case.st.kv_dtype], f"max abs err {err:.3e} ({M.last_kernel()})"
+    return err, dc
+
+
+def small_decode(kv_dtype, seed=7, **kw):
+    base = dict(B=5, Hq=8, Hkv=2, D=128, P=16, theta=5e5, q_dtype="f32" if kv_dtype == "f32" else "bf16",
+                kv_dtype=kv_dtype, prefix=48, n_chunks=(1, 4), chunk_tokens=160, pool=4, question=37)
+    base.update(kw)
+    return W.decode_structure(f"small_decode_{kv_dtype}", seed, **base)
+
+
+BOTH_PATHS = [0, 2]  # 2 = FLAG_FORCE_GENERAL
+
+
+def test_config1_tiny_decode_fp32(mepic, oracle_attn):
+    case = build_case(mepic, W.config(1))
+    assert case.kv_lens.tolist() == [289] and case.n_blocks.tolist() == [19]
+    check(mepic, oracle_attn, case)
+
+
+@pytest.mark.parametrize("flags", BOTH_PATHS)
+@pytest.mark.parametrize("kv_dtype", ["f32", "bf16", "f8e4m3"])
+def test_small_decode_all_dtypes(mepic, oracle_attn, kv_dtype, flags):
+    P = 32 if kv_dtype == "f8e4m3" else 16
+    check(mepic, oracle_attn, build_case(mepic, small_decode(kv_dtype, P=P)), flags=flags)
+
+
+@pytest.mark.parametrize("flags", BOTH_PATHS)
+def test_decode_gqa7_fp8_page32(mepic, oracle_attn, flags):
+    """Head shapes of the mixed-length config: 28 query heads on 4 KV heads, page 32, theta 1e6."""
+    st = W.decode_structure("small_cfg5", 11, B=9, Hq=28, Hkv=4, D=128, P=32, theta=1e6, q_dtype="bf16",
+                            kv_dtype="f8e4m3", prefix=0, n_chunks=(1, 9), chunk_tokens=512, pool=6, question=0)
+    check(mepic, oracle_attn, build_case(mepic, st), flags=flags)
+
+
+@pytest.mark.parametrize("flags", BOTH_PATHS)
+def test_decode_long_context_many_splits(mepic, oracle_attn, flags):
+    """One long request next to short ones: several splits, ragged last split, positions up to ~20K."""
+    st = W.decode_structure("long_short", 13, B=3, Hq=32, Hkv=8, D=128, P=16, theta=5e5, q_dtype="bf16",
+                            kv_dtype="bf16", prefix=0, n_chunks=(1, 20), chunk_tokens=1024, pool=5, question=19)
+    check(mepic, oracle_attn, build_case(mepic, st), flags=flags)
+
+
+@pytest.mark.parametrize("D,P", [(64, 16), (64, 32), (128, 32)])
+@pytest.mark.parametrize("kv_dtype", ["f32", "bf16"])
+def test_decode_other_shapes(mepic, oracle_attn, kv_dtype, D, P):
+    st = small_decode(kv_dtype, D=D, P=P, Hq=6, Hkv=3, theta=1e4, chunk_tokens=96)
+    check(mepic, oracle_attn, build_case(mepic, st))
+
+
+@pytest.mark.parametrize("kv_dtype", ["f32", "bf16"])
+def test_interleaved_pairing_and_explicit_scale(mepic, oracle_attn, kv_dtype):
+    case = build_case(mepic, small_decode(kv_dtype, seed=3))
+    check(mepic, oracle_attn, case, interleaved=True)
+    check(mepic, oracle_attn, case, sm_scale=0.05)
+
+
+@pytest.mark.parametrize("kv_dtype", ["f32", "bf16", "f8e4m3"])
+@pytest.mark.parametrize("pads_are_positions", [True, False])
+def test_ragged_segments_with_pads_both_readings(mepic, oracle_attn, kv_dtype, pads_are_positions):
+    """Segment lengths that are not multiples of the page: leading pads in chunks, trailing pads in prompts.
+    Reading 1: pads are ordinary slots. Reading 2: the aligner's valid masks and pad-free positions are used."""
+    P = 32 if kv_dtype == "f8e4m3" else 16
+    st = W.Structure("ragged", "decode", 3, 8, 2, 128, P, 1e4, "f32" if kv_dtype == "f32" else "bf16", kv_dtype, 21)
+    C = W.CHUNK_KEY_BASE
+    st.requests = [[(0, 35, 0), (1, 100, C + 1), (0, 7, 0), (1, 45, C + 2), (0, 20, 0)],
+                   [(1, 45, C + 2), (1, 100, C + 1)],
+                   [(0, 3, 0)]]
+    st.n_q = [1, 1, 1]
+    case = build_case(mepic, st, pads_are_positions=pads_are_positions)
+    assert (case.block_valid_mask is None) == pads_are_positions
+    check(mepic, oracle_attn, case)
+
+
+def test_prefill_small_fp32_and_bf16(mepic, oracle_attn):
+    for kv_dtype, flags in (("f32", 0), ("bf16", 0), ("bf16", 2)):
+        st = W.prefill_structure("small_prefill", 17, B=3, Hq=8, Hkv=2, D=128, P=16, theta=5e5, n_chunks=3,
+                                 chunk_tokens=144, pool=4, q_tokens=70, max_gap_pages=2,
+                                 q_dtype="f32" if kv_dtype == "f32" else "bf16", kv_dtype=kv_dtype)
+        check(mepic, oracle_attn, build_case(mepic, st), flags=flags)
+
+
+def test_prefill_ragged_query_counts(mepic, oracle_attn):
+    st = W.prefill_structure("ragged_prefill", 19, B=4, Hq=32, Hkv=8, D=128, P=16, theta=5e5, n_chunks=2,
+                             chunk_tokens=256, pool=3, q_tokens=1)
+    st.n_q = [1, 33, 64, 7]
+    for b, n in enumerate(st.n_q):
+        st.requests[b][-1] = (0, n + 5 * b, 0)          # the question segment is longer than the query count
+    check(mepic, oracle_attn, build_case(mepic, st))
+
+
+def test_empty_and_degenerate_requests(mepic, oracle_attn):
+    """kv_len 0 (all-zero output row), kv_len 1 (output = that V row), and an empty batch."""
+    st = W.Structure("degenerate", "decode", 3, 8, 2, 128, 16, 1e4, "bf16", "bf16", 23)
+    st.requests = [[(0, 1, 0)], [(0, 1, 0)], [(0, 40, 0)]]
+    st.extra_tail = 0
+    st.n_q = [1, 1, 1]
+    case = build_case(mepic, st)
+    case.kv_lens[0] = 0
+    err, dc = check(mepic, oracle_attn, case)
+    out = dc.out.float().cpu().numpy()
+    assert (out[0] == 0).all()
+    v_row = W.unpack_v(case.pages.v)[case.block_tables[1, 0], :, 0, :].float().numpy()   # [Hkv, D], slot 0
+    assert np.array_equal(out[1], np.repeat(v_row, 4, axis=0))
+    # B = 0: nothing to do, no launch, no error
+    z = torch.zeros((0, 8, 128), dtype=torch.bfloat16, device="cuda")
+    zi = torch.zeros((0,), dtype=torch.int32, device="cuda")
+    p = mepic.make_params(z, z.clone(), dc.k, dc.v, torch.zeros((0, 4), dtype=torch.int32, device="cuda"), zi, zi,
+                          rope_theta=1e4, workspace=dc.ws)
+    mepic.attn_decode(p)
+
+
+@pytest.mark.parametrize("kv_dtype", ["bf16", "f8e4m3"])
+def test_shared_and_duplicated_layouts_agree_bitwise(mepic, oracle_attn, kv_dtype):
+    """Sharing pages changes nothing numerically: the work split depends on the logical shape only."""
+    P = 32 if kv_dtype == "f8e4m3" else 16
+    case = build_case(mepic, small_decode(kv_dtype, P=P, B=8, pool=2), poison=False)
+    dup = W.to_duplicated(case)
+    assert dup.pages.num_pages == int(case.n_blocks.sum()) > case.pages.num_pages
+    a = DeviceCase(mepic, case).run()
+    b = DeviceCase(mepic, dup).run()
+    assert np.array_equal(a, b)
+    assert np.abs(a - oracle_out(oracle_attn, dup)).max() <= TOL[kv_dtype]
+
+
+def test_chunk_twice_in_one_request_uses_request_positions(mepic, oracle_attn):
+    """The same shared pages at two offsets of one block table: rotation must follow the request's positions."""
+    st = W.Structure("twice", "decode", 1, 8, 2, 128, 16, 5e5, "bf16", "bf16", 29)
+    C = W.CHUNK_KEY_BASE
+    st.requests = [[(1, 256, C + 1), (0, 16, 0), (1, 256, C + 1), (1, 256, C + 1)]]
+    st.n_q = [1]
+    case = build_case(mepic, st)
+    bt = case.block_tables[0]
+    assert bt[1:16].tolist() == bt[18:33].tolist() == bt[34:49].tolist()
+    check(mepic, oracle_attn, case)
+
+
+# ------------------------------------------------------------------ the BASELINE configs at full size
+def sample_rows(case, n, seed=0):
+    rng = np.random.default_rng(seed)
+    nq, Hq = case.n_q, case.st.Hq
+    rows = {(0, 0), (nq - 1, Hq - 1)}
+    while len(rows) < min(n, nq * Hq):
+        rows.add((int(rng.integers(nq)), int(rng.integers(Hq))))
+    return sorted(rows)
+
+
+@pytest.mark.parametrize("cfg,n_rows", [(2, 96), (4, 24), (5, 64)])
+def test_full_size_decode_configs_sampled(mepic, oracle_attn, cfg, n_rows):
+    """Configs 2, 4, 5 at full size in the launch configuration the bench times; sampled rows against the
+    oracle, every row finite, shared vs duplicated layout bitwise equal."""
+    case = build_case(mepic, W.config(cfg))
+    err, dc = check(mepic, oracle_attn, case, rows=sample_rows(case, n_rows))
+    out = dc.out.float()
+    assert torch.isfinite(out).all()
+    if cfg == 2:
+        dup = DeviceCase(mepic, W.to_duplicated(case))
+        assert torch.equal(torch.from_numpy(dup.run()), out.double().cpu())
+
+
+def test_full_size_prefill_config3_sampled(mepic, oracle_attn):
+    case = build_case(mepic, W.config(3))
+    check(mepic, oracle_attn, case, rows=sample_rows(case, 48))
