@@ -1,0 +1,185 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused-RoPE paged-attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--layout both|shared|duplicated]
+
+A step is one attention call of the library over the whole batch of the workload (gather through the
+block tables, rotary embedding of K and Q on chip, online softmax, PV, split-K combine), with every
+input already resident in HBM. Block tables come from the library's own aligner before the timed
+region (the scheduling path runs once per request, not once per decode step); its cost is reported
+separately. The default workload is the Llama-3-8B-shaped decode configuration of the benchmark spec.
+
+Prints ONE JSON line. `value` is logical KV bytes per second on the page-sharing (MEPIC) layout;
+`roofline` is measured on the same logical workload laid out with one page per logical block, where
+every byte has to come from HBM (shared pages can be served from the caches).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def algorithmic_bytes(case) -> int:
+    """Bytes the method must move per call: K and V of every addressed slot, block-table entries,
+    per-page scales (fp8), q in and out. No rotated copy of K, no cos/sin table."""
+    st = case.st
+    qb = 4 if st.q_dtype == "f32" else 2
+    n = case.kv_bytes_logical()
+    n += int(case.n_blocks.sum()) * 4
+    if st.kv_dtype == "f8e4m3":
+        n += int(case.n_blocks.sum()) * 8
+    n += 2 * case.n_q * st.Hq * st.D * qb
+    return n
+
+
+def visible_pairs(case) -> int:
+    """(query, key) pairs that take part, per query head (prefill: causal by position)."""
+    import numpy as np
+    if case.cu_q_lens is None:
+        return int(case.kv_lens.astype(np.int64).sum())
+    total = 0
+    for b in range(case.st.B):
+        pos = case.q_positions[case.cu_q_lens[b]:case.cu_q_lens[b + 1]].astype(np.int64)
+        total += int(np.minimum(pos + 1, int(case.kv_lens[b])).sum())
+    return total
+
+
+def time_steps(dc, steps: int, warmup: int):
+    """Run warmup + steps calls on torch's current stream; HIP events bracket the timed region and every
+    single step. Returns (total ms, list of per-step ms)."""
+    import torch
+    run = dc.M.attn_prefill if dc.prefill else dc.M.attn_decode
+    for _ in range(warmup):
+        run(dc.params)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    ev[0].record()
+    for i in range(steps):
+        run(dc.params)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    per = [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]
+    return ev[0].elapsed_time(ev[steps]), per
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, help="BASELINE.json config (1-based); default 2")
+    ap.add_argument("--layout", default="both", choices=["both", "shared", "duplicated"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=0, help="oracle sample size in (token, head) rows")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2512_16822_amd as M
+    import workloads as W
+    from harness import DeviceCase, align_with_library
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    M.load()
+    st = W.config(args.config)
+
+    # ---- scheduling path (host): align every request, report the accounting ----
+    t0 = time.perf_counter()
+    aligned, pool = align_with_library(M, st)
+    align_s = time.perf_counter() - t0
+    stats = pool.stats()
+    case = W.assemble(st, aligned, poison=False)
+    prefill = st.mode == "prefill"
+
+    results = {}
+    layouts = ["shared", "duplicated"] if args.layout == "both" else [args.layout]
+    for layout in layouts:
+        c = case if layout == "shared" else W.to_duplicated(case)
+        dc = DeviceCase(M, c)
+        total_ms, per = time_steps(dc, args.steps, args.warmup)
+        results[layout] = dict(ms=total_ms / args.steps, min_ms=min(per), kernel=M.last_kernel(),
+                               pages=c.pages.num_pages, out=dc.out.float().cpu())
+        del dc
+        torch.cuda.empty_cache()
+    if len(layouts) == 2:
+        assert torch.equal(results["shared"]["out"], results["duplicated"]["out"]), "layouts disagree"
+
+    abytes = algorithmic_bytes(case)
+    flops = 4 * st.D * visible_pairs(case) * st.Hq
+    main_layout = "shared" if "shared" in results else layouts[0]
+    roof_layout = "duplicated" if "duplicated" in results else layouts[0]
+    ms = results[main_layout]["ms"]
+    if prefill:
+        value, unit, metric = flops / (ms * 1e-3) / 1e12, "TFLOP/s", "fused-RoPE paged prefill attention throughput"
+        rms = results[roof_layout]["ms"]
+        ach = flops / (rms * 1e-3) / 1e12
+        roofline = dict(bound="mfma", achieved=ach, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
+                        frac=ach / MFMA_BF16_PEAK_TFLOPS, traffic=None, layout=roof_layout,
+                        kernel=results[roof_layout]["kernel"], kernel_ms=rms)
+    else:
+        value, unit, metric = abytes / (ms * 1e-3) / 1e9, "GB/s", "fused-RoPE paged decode attention KV throughput"
+        rms = results[roof_layout]["ms"]
+        ach = abytes / (rms * 1e-3) / 1e9
+        roofline = dict(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS,
+                        traffic=None, layout=roof_layout, kernel=results[roof_layout]["kernel"], kernel_ms=rms)
+
+    # ---- the oracle on this machine's host cores, on a bounded sample of the same workload ----
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import attn as oracle_attn
+        from oracle import align as oracle_align
+        from harness import oracle_out
+        opool = oracle_align.PoolOracle(1 << 20, st.P)
+        o_aligned = [opool.align(segs, st.extra_tail) for segs in st.requests]
+        assert all(a["block_table"] == b["block_table"].tolist() for a, b in zip(o_aligned, aligned))
+        n_rows_total = case.n_q * st.Hq
+        # about 20 CPU-seconds of oracle work: ~2 us per (row, key) at D = 128 on these hosts
+        n_rows = args.cpu_rows or max(8, min(n_rows_total, int(1.0e7 / max(1, int(case.kv_lens.mean())))))
+        rng = np.random.default_rng(0)
+        rows = sorted({(int(rng.integers(case.n_q)), int(rng.integers(st.Hq))) for _ in range(n_rows)})
+        t0 = time.perf_counter()
+        want = oracle_out(oracle_attn, case, rows=rows)
+        cpu_s = time.perf_counter() - t0
+        got = results[main_layout]["out"].double().numpy()
+        err = float(np.abs(np.stack([got[t, h] for t, h in rows]) - want).max())
+        scale = n_rows_total / len(rows)
+        whole = cpu_s * scale
+        cpu = dict(value=(flops / whole / 1e12) if prefill else (abytes / whole / 1e9), unit=unit,
+                   cores=oracle_attn.num_threads(), kind="oracle",
+                   sample=f"{len(rows)} of {n_rows_total} (query token, head) rows in {cpu_s:.2f} s, scaled to the whole job",
+                   max_abs_err_of_gpu_on_sample=err)
+
+    line = dict(metric=metric, value=value, unit=unit, n_gpus=1, steps=args.steps, warmup=args.warmup,
+                ms_per_step=ms, higher_is_better=True, scaling="weak", vs_baseline=None,
+                dtype={"f32": "f32", "bf16": "bf16", "f8e4m3": "bf16 (fp8 e4m3 KV)"}[st.kv_dtype],
+                data="synthetic",
+                config=dict(workload=st.name, layout=main_layout, B=st.B, Hq=st.Hq, Hkv=st.Hkv, D=st.D, P=st.P,
+                            kv_len_mean=float(case.kv_lens.mean()), kv_len_max=int(case.kv_lens.max()),
+                            n_q_tokens=case.n_q, algorithmic_bytes=abytes, useful_flops=flops),
+                roofline=roofline, cpu_baseline=cpu,
+                layouts={k: dict(ms_per_step=v["ms"], min_ms=v["min_ms"], pages=v["pages"], kernel=v["kernel"],
+                                 gbs=abytes / (v["ms"] * 1e-3) / 1e9) for k, v in results.items()},
+                accounting=dict(pages_unique=stats["pages_in_use_unique"],
+                                pages_duplicated=stats["pages_logical_duplicated"],
+                                ratio=stats["pages_logical_duplicated"] / max(1, stats["pages_in_use_unique"]),
+                                aligner_us_per_request=align_s / max(1, st.B) * 1e6))
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
