@@ -43,9 +43,27 @@ Plan make_plan(const mepic_attn_params* p, bool prefill) {
   const int n_blocks = (max_kv + p->P - 1) / p->P;
   const bool plain = !p->block_positions && !p->block_valid_mask &&
                      !(p->flags & (MEPIC_FLAG_ROPE_INTERLEAVED | MEPIC_FLAG_FORCE_GENERAL));
-  (void)G;
-  (void)plain;
   pl.kernel = K_GENERAL;
+
+  if (!prefill && plain && G <= 16 && p->q_dtype == MEPIC_BF16 && p->kv_dtype == MEPIC_BF16 && p->D == 128 &&
+      p->P == 16) {
+    // Matrix-core decode: one wave per (request, KV head, split), one wave per SIMD at a time. Aim at a few
+    // waves per SIMD over the run so the tail is short, but keep a split long enough (>= 16 blocks) to
+    // amortise the per-wave set-up of the rotary constants. Splits hold an even number of blocks.
+    pl.kernel = K_DECODE_MFMA_BF16;
+    const long pairs = (long)p->B * p->Hkv;
+    int want = pairs > 0 ? (int)((4096 + pairs - 1) / pairs) : 1;
+    const int max_splits = (n_blocks + 15) / 16;
+    if (want > max_splits) want = max_splits;
+    if (want < 1) want = 1;
+    int bps = (n_blocks + want - 1) / want;
+    bps = (bps + 1) & ~1;
+    if (bps < 2) bps = 2;
+    pl.blocks_per_split = bps;
+    pl.n_splits = n_blocks > 0 ? (n_blocks + bps - 1) / bps : 1;
+    pl.workspace_bytes = (size_t)p->n_q_tokens * p->Hq * pl.n_splits * (p->D + 2) * sizeof(float);
+    return pl;
+  }
 
   // General path: one workgroup per (query token, KV head, split); a split is a whole number of
   // 256-slot tiles. Enough splits to put ~8 workgroups on each of the 256 compute units.
@@ -106,6 +124,11 @@ int run(const mepic_attn_params* p, void* hip_stream, bool prefill) {
   hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
   hipError_t e = hipSuccess;
   switch (pl.kernel) {
+    case K_DECODE_MFMA_BF16:
+      g_last_kernel = "decode_mfma_bf16";
+      e = launch_decode_mfma_bf16(a, s);
+      if (e == hipSuccess) e = launch_combine(a, s);
+      break;
     default:
       g_last_kernel = "general";
       e = launch_general(a, s);
