@@ -47,21 +47,12 @@ Plan make_plan(const mepic_attn_params* p, bool prefill) {
 
   if (!prefill && plain && G <= 16 && p->q_dtype == MEPIC_BF16 && p->kv_dtype == MEPIC_BF16 && p->D == 128 &&
       p->P == 16) {
-    // Matrix-core decode: one wave per (request, KV head, split), one wave per SIMD at a time. Aim at a few
-    // waves per SIMD over the run so the tail is short, but keep a split long enough (>= 16 blocks) to
-    // amortise the per-wave set-up of the rotary constants. Splits hold an even number of blocks.
+    // Matrix-core decode: persistent waves cut each KV head's sequence of steps into equal chunks; here only
+    // the bound on partials per request (sizes the workspace) and the minimum chunk are fixed.
     pl.kernel = K_DECODE_MFMA_BF16;
-    const long pairs = (long)p->B * p->Hkv;
-    int want = pairs > 0 ? (int)((4096 + pairs - 1) / pairs) : 1;
-    const int max_splits = (n_blocks + 15) / 16;
-    if (want > max_splits) want = max_splits;
-    if (want < 1) want = 1;
-    int bps = (n_blocks + want - 1) / want;
-    bps = (bps + 1) & ~1;
-    if (bps < 2) bps = 2;
-    pl.blocks_per_split = bps;
-    pl.n_splits = n_blocks > 0 ? (n_blocks + bps - 1) / bps : 1;
-    pl.workspace_bytes = (size_t)p->n_q_tokens * p->Hq * pl.n_splits * (p->D + 2) * sizeof(float);
+    decode_mfma_plan(p->B, p->Hkv, max_kv, &pl.n_splits, &pl.blocks_per_split);
+    pl.workspace_bytes = (size_t)p->n_q_tokens * p->Hq * pl.n_splits * (p->D + 2) * sizeof(float) +
+                         (size_t)(p->B + 2) * sizeof(int32_t);
     return pl;
   }
 
@@ -120,6 +111,7 @@ int run(const mepic_attn_params* p, void* hip_stream, bool prefill) {
   float* ws = reinterpret_cast<float*>(p->workspace);
   a.part_o = ws;
   a.part_ml = ws + (size_t)a.n_q * a.Hq * a.n_splits * a.D;
+  a.part_meta = reinterpret_cast<int32_t*>(a.part_ml + (size_t)a.n_q * a.Hq * a.n_splits * 2);
 
   hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
   hipError_t e = hipSuccess;
@@ -127,7 +119,6 @@ int run(const mepic_attn_params* p, void* hip_stream, bool prefill) {
     case K_DECODE_MFMA_BF16:
       g_last_kernel = "decode_mfma_bf16";
       e = launch_decode_mfma_bf16(a, s);
-      if (e == hipSuccess) e = launch_combine(a, s);
       break;
     default:
       g_last_kernel = "general";

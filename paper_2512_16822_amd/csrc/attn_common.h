@@ -27,6 +27,7 @@ struct AttnArgs {
   const uint32_t* block_valid_mask;  // nullable
   float* part_o;                     // [n_q][Hq][n_splits][D] un-normalised partial outputs
   float* part_ml;                    // [n_q][Hq][n_splits][2] running max (log2 units) and sum
+  int32_t* part_meta;                // stream-K decode: steps before each request [B+1], then the chunk
   int32_t B, n_q, Hq, Hkv, D, P, max_blocks, num_pages, G;
   int32_t q_dtype, kv_dtype;
   int32_t interleaved, causal;
@@ -64,6 +65,7 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float x) {
 // Launchers (host). Each returns a hipError_t from the launch.
 hipError_t launch_general(const AttnArgs& a, hipStream_t s);
 hipError_t launch_combine(const AttnArgs& a, hipStream_t s);
-hipError_t launch_decode_mfma_bf16(const AttnArgs& a, hipStream_t s);
+hipError_t launch_decode_mfma_bf16(const AttnArgs& a, hipStream_t s);  // includes its merge kernel
+void decode_mfma_plan(int B, int Hkv, int max_kv_len, int* max_splits, int* min_chunk);
 
 }  // namespace mepic

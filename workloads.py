@@ -256,16 +256,24 @@ def poison_tail(pages: KVPages, block_tables: np.ndarray, kv_lens: np.ndarray) -
             pages.v[page, :, :, s0:] = float("nan")
 
 
-def duplicate_layout(pages: KVPages, block_tables: np.ndarray, n_blocks: np.ndarray):
+def duplicate_layout(pages: KVPages, block_tables: np.ndarray, n_blocks: np.ndarray, shuffle_seed=None):
     """Materialise the same logical KV with one page per logical block (no sharing).
 
-    Returns (KVPages with sum(n_blocks) pages, block table of the same shape pointing at them)."""
+    Pages are handed out in request order, or in a seeded random order when `shuffle_seed` is given (a pool
+    that has been in use for a while). Returns (KVPages with sum(n_blocks) pages, block table of the same
+    shape pointing at them)."""
     B, max_blocks = block_tables.shape
-    src = np.concatenate([block_tables[b, : n_blocks[b]] for b in range(B)]).astype(np.int64)
+    src_logical = np.concatenate([block_tables[b, : n_blocks[b]] for b in range(B)]).astype(np.int64)
+    total = int(src_logical.size)
+    place = np.arange(total, dtype=np.int64)          # logical block i lives in physical page place[i]
+    if shuffle_seed is not None:
+        place = _rng(shuffle_seed, 5).permutation(total)
+    src = np.empty(total, dtype=np.int64)             # physical page p holds the content of old page src[p]
+    src[place] = src_logical
     bt = np.zeros_like(block_tables)
     o = 0
     for b in range(B):
-        bt[b, : n_blocks[b]] = np.arange(o, o + n_blocks[b], dtype=block_tables.dtype)
+        bt[b, : n_blocks[b]] = place[o:o + n_blocks[b]].astype(block_tables.dtype)
         o += int(n_blocks[b])
     idx = torch.from_numpy(src)
     ks = pages.k_scales[idx].contiguous() if pages.k_scales is not None else None
@@ -356,8 +364,8 @@ def assemble(st: Structure, aligned: List[dict], *, pads_are_positions: bool = T
                 np.array(cu, dtype=np.int32) if st.mode == "prefill" else None, pages, q, bp, bm)
 
 
-def to_duplicated(case: Case) -> Case:
+def to_duplicated(case: Case, shuffle_seed=None) -> Case:
     """The same logical case with one page per logical block."""
-    pages, bt = duplicate_layout(case.pages, case.block_tables, case.n_blocks)
+    pages, bt = duplicate_layout(case.pages, case.block_tables, case.n_blocks, shuffle_seed)
     return Case(case.st, bt, case.n_blocks, case.kv_lens, case.q_positions, case.cu_q_lens, pages, case.q,
                 case.block_positions, case.block_valid_mask)
