@@ -56,6 +56,20 @@ Plan make_plan(const mepic_attn_params* p, bool prefill) {
     return pl;
   }
 
+  if (prefill && plain && p->q_dtype == MEPIC_BF16 && p->kv_dtype == MEPIC_BF16 && p->D == 128 && p->P == 16 &&
+      prefill_mfma_rows_per_workgroup() % G == 0) {
+    // Matrix-core prefill: one workgroup per (request, KV head, tile of 256 query rows); no split over KV, the
+    // output is written directly.
+    pl.kernel = K_PREFILL_MFMA_BF16;
+    const int max_q = p->max_q_len > 0 && p->max_q_len < p->n_q_tokens ? p->max_q_len : p->n_q_tokens;
+    const int tok_per_wg = prefill_mfma_rows_per_workgroup() / G;
+    pl.n_splits = (max_q + tok_per_wg - 1) / tok_per_wg;
+    if (pl.n_splits < 1) pl.n_splits = 1;
+    pl.blocks_per_split = n_blocks;
+    pl.workspace_bytes = 0;
+    return pl;
+  }
+
   // General path: one workgroup per (query token, KV head, split); a split is a whole number of
   // 256-slot tiles. Enough splits to put ~8 workgroups on each of the 256 compute units.
   const int tile_blocks = 256 / p->P;
@@ -119,6 +133,10 @@ int run(const mepic_attn_params* p, void* hip_stream, bool prefill) {
     case K_DECODE_MFMA_BF16:
       g_last_kernel = "decode_mfma_bf16";
       e = launch_decode_mfma_bf16(a, s);
+      break;
+    case K_PREFILL_MFMA_BF16:
+      g_last_kernel = "prefill_mfma_bf16";
+      e = launch_prefill_mfma_bf16(a, s);
       break;
     default:
       g_last_kernel = "general";
