@@ -45,19 +45,19 @@ Plan make_plan(const mepic_attn_params* p, bool prefill) {
                      !(p->flags & (MEPIC_FLAG_ROPE_INTERLEAVED | MEPIC_FLAG_FORCE_GENERAL));
   pl.kernel = K_GENERAL;
 
-  if (!prefill && plain && G <= 16 && p->q_dtype == MEPIC_BF16 && p->kv_dtype == MEPIC_BF16 && p->D == 128 &&
-      p->P == 16) {
+  const bool mfma_bf16 = p->q_dtype == MEPIC_BF16 && p->kv_dtype == MEPIC_BF16 && p->D == 128 && p->P == 16;
+  const bool mfma_fp8 = p->q_dtype == MEPIC_BF16 && p->kv_dtype == MEPIC_F8E4M3 && p->D == 128 && p->P == 32;
+  if (!prefill && plain && G <= 16 && (mfma_bf16 || mfma_fp8)) {
     // Matrix-core decode: persistent waves cut each KV head's sequence of steps into equal chunks; here only
     // the bound on partials per request (sizes the workspace) and the minimum chunk are fixed.
-    pl.kernel = K_DECODE_MFMA_BF16;
+    pl.kernel = mfma_fp8 ? K_DECODE_MFMA_F8 : K_DECODE_MFMA_BF16;
     decode_mfma_plan(p->B, p->Hkv, max_kv, &pl.n_splits, &pl.blocks_per_split);
     pl.workspace_bytes = (size_t)p->n_q_tokens * p->Hq * pl.n_splits * (p->D + 2) * sizeof(float) +
                          (size_t)(p->B + 2) * sizeof(int32_t);
     return pl;
   }
 
-  if (prefill && plain && p->q_dtype == MEPIC_BF16 && p->kv_dtype == MEPIC_BF16 && p->D == 128 && p->P == 16 &&
-      prefill_mfma_rows_per_workgroup() % G == 0) {
+  if (prefill && plain && mfma_bf16 && prefill_mfma_rows_per_workgroup() % G == 0) {
     // Matrix-core prefill: one workgroup per (request, KV head, tile of 256 query rows); no split over KV, the
     // output is written directly.
     pl.kernel = K_PREFILL_MFMA_BF16;
@@ -131,8 +131,9 @@ int run(const mepic_attn_params* p, void* hip_stream, bool prefill) {
   hipError_t e = hipSuccess;
   switch (pl.kernel) {
     case K_DECODE_MFMA_BF16:
-      g_last_kernel = "decode_mfma_bf16";
-      e = launch_decode_mfma_bf16(a, s);
+    case K_DECODE_MFMA_F8:
+      g_last_kernel = pl.kernel == K_DECODE_MFMA_F8 ? "decode_mfma_fp8" : "decode_mfma_bf16";
+      e = launch_decode_mfma(a, s);
       break;
     case K_PREFILL_MFMA_BF16:
       g_last_kernel = "prefill_mfma_bf16";

@@ -1,4 +1,7 @@
-// Matrix-core decode kernel of fused-RoPE paged attention (§3.3.3) for bf16 K/V, D = 128, P = 16.
+// Matrix-core decode kernels of fused-RoPE paged attention (§3.3.3), D = 128:
+//   bf16 K/V pages of 16 slots (a step = two pages), and
+//   fp8 e4m3 K/V pages of 32 slots with one fp32 scale per page for K and for V (a step = one page).
+// The text below describes the bf16 kernel; the fp8 variant differs where noted at the end.
 //
 // Persistent waves, stream-K over pages. The grid is one workgroup of four waves per compute unit (one
 // wave per SIMD: measured faster than two, whose smaller register budget costs prefetch depth). Workgroup g serves KV head g % Hkv (consecutive workgroups land on consecutive
@@ -26,6 +29,14 @@
 // product), which makes each lane end up with the scores of 8 consecutive slots of one page for one
 // head — exactly the A operand of the PV product, so probabilities never leave their lane, and the
 // matching V operand is one contiguous 16-byte piece of a V page row.
+//
+// fp8 variant: a lane owns dims 16kg..16kg+15 and 64+16kg.. (two 16-byte K granules per row); K is widened
+// with v_cvt_pk_f32_fp8, rotated, rounded to bf16 for the same QK products, and the page's K scale multiplies
+// the scores. V is never widened: PV runs on v_mfma_f32_16x16x32_fp8_fp8 with the V bytes as loaded (8 bytes
+// per lane and column tile) and the probabilities split into two e4m3 terms (p*4 = hi + lo, 8 significant
+// bits together); each step's product goes to a scratch accumulator and enters O scaled by the page's V scale.
+#include <type_traits>
+
 #include "attn_common.h"
 
 namespace mepic {
@@ -36,7 +47,7 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-constexpr int kD = 128, kP = 16;
+constexpr int kD = 128;
 constexpr int kWaves = 4;             // waves per workgroup
 #ifndef MEPIC_DECODE_WG_PER_CU
 #define MEPIC_DECODE_WG_PER_CU 1
@@ -65,6 +76,9 @@ __device__ __forceinline__ int sload(const int32_t* p, size_t idx) {
   return ((const_i32_ptr)(uintptr_t)p)[idx];
 }
 
+typedef const __attribute__((address_space(4))) float* const_f32_ptr;
+__device__ __forceinline__ float sloadf(const float* p, size_t idx) { return ((const_f32_ptr)(uintptr_t)p)[idx]; }
+
 // Maximum over the four lanes l, l^16, l^32, l^48 (the four k-groups of one head), in every lane.
 __device__ __forceinline__ float max_over_kgroups(float x) {
   const uint32_t u = __float_as_uint(x);
@@ -83,10 +97,17 @@ __device__ __forceinline__ float sum_over_kgroups(float x) {
   return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
-__global__ __launch_bounds__(64 * kWaves, kWgPerCu) void decode_mfma_bf16_kernel(const AttnArgs a) {
+constexpr float kPScaleFp8 = 4.f;     // probabilities (< 2^slack = 64) are multiplied by this before the e4m3 split
+
+template <bool kFp8>
+__global__ __launch_bounds__(64 * kWaves, kWgPerCu) void decode_mfma_kernel(const AttnArgs a) {
+  constexpr int kP = kFp8 ? 32 : 16;          // slots per page
+  constexpr int kBps = kFp8 ? 1 : 2;          // blocks (pages) per step of 32 slots
+  constexpr int kNK = kFp8 ? 2 : 4;           // 16-byte K fragments per lane and product
+  typedef typename std::conditional<kFp8, uint2, uint4>::type VRaw;  // V fragment per lane and column tile
   // Rotation constants, identical for every wave: one float4 {c0, s0, c1, s1} per lane and element pair.
-  __shared__ float4 rotK[16][64];  // slot rotation R(slot32): index (u*2 + jj)*4 + w
-  __shared__ float4 rotS[8][64];   // step rotation R(-32):    index jj*4 + w
+  __shared__ float4 rotK[16][64];  // slot rotation R(slot32): index (u*2 + h)*4 + w
+  __shared__ float4 rotS[8][64];   // step rotation R(-32):    index h*4 + w
   extern __shared__ int cum[];     // cum[b] = steps of the requests before b; B + 1 entries
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n16 = lane & 15, kg = lane >> 4;
@@ -98,7 +119,7 @@ __global__ __launch_bounds__(64 * kWaves, kWgPerCu) void decode_mfma_bf16_kernel
     for (int base = 0; base < a.B; base += 64) {
       const int b = base + lane;
       int x = 0;
-      if (b < a.B) x = ((a.kv_lens[b] + kP - 1) / kP + 1) / 2;
+      if (b < a.B) x = ((a.kv_lens[b] + kP - 1) / kP + kBps - 1) / kBps;
 #pragma unroll
       for (int o = 1; o < 64; o <<= 1) {
         const int y = __shfl_up(x, o);
@@ -110,13 +131,14 @@ __global__ __launch_bounds__(64 * kWaves, kWgPerCu) void decode_mfma_bf16_kernel
     if (lane == 0) cum[0] = 0;
   }
   // ---- rotation constants. As holder of K rows, row n16 of product u is slot32 = 8*(n16/4) + 4u + n16%4 of
-  // the step; as holder of 8-element column chunks a lane owns frequencies i = 32*jj + 8*kg + e (dims i and
-  // i + 64 are the rotary pair and sit in k-steps jj and jj + 2 of the same lane). ----
+  // the step. A lane owns 16 rotary pairs p = 8h + e (h in {0,1}, e < 8): frequency i(p) = 32h + 8kg + e for
+  // bf16 (dims i and i + 64 sit in k-steps h and h + 2), i(p) = 16kg + p for fp8. ----
+  auto freq_of = [&](int pidx) { return kFp8 ? 16 * kg + pidx : 32 * (pidx >> 3) + 8 * kg + (pidx & 7); };
   const int slot_u0 = 8 * (n16 >> 2) + (n16 & 3);
   for (int idx = wave; idx < 24; idx += kWaves) {
-    const int jj = (idx >> 2) & 1, w = idx & 3;  // idx = (u*2 + jj)*4 + w for rotK, 16 + jj*4 + w for rotS
+    const int h = (idx >> 2) & 1, w = idx & 3;  // idx = (u*2 + h)*4 + w for rotK, 16 + h*4 + w for rotS
     const float pos = idx < 16 ? (float)(slot_u0 + 4 * (idx >> 3)) : -32.0f;
-    const int i = 32 * jj + 8 * kg + 2 * w;
+    const int i = freq_of(8 * h + 2 * w);     // pairs 8h + 2w and 8h + 2w + 1 have consecutive frequencies
     const float t0 = turns_frac(pos, a.freq_hi[i], a.freq_lo[i]);
     const float t1 = turns_frac(pos, a.freq_hi[i + 1], a.freq_lo[i + 1]);
     const float4 r = make_float4(__builtin_amdgcn_cosf(t0), __builtin_amdgcn_sinf(t0), __builtin_amdgcn_cosf(t1),
@@ -137,41 +159,58 @@ __global__ __launch_bounds__(64 * kWaves, kWgPerCu) void decode_mfma_bf16_kernel
   if (pos_begin >= pos_end) return;
 
   const uint4* kpages = reinterpret_cast<const uint4*>(a.k_pages);
-  const uint4* vpages = reinterpret_cast<const uint4*>(a.v_pages);
+  const VRaw* vpages = reinterpret_cast<const VRaw*>(a.v_pages);
   const uint4* q4 = reinterpret_cast<const uint4*>(a.q);
 
   floatx4 o[8];
   float m_run, l_part;
-  float qlo[2][8], qhi[2][8];  // Q' of head n16 for the lane's 16 rotary pairs, in log2 units
+  float qlo[2][8], qhi[2][8];  // Q' of head n16 for the lane's 16 rotary pairs [h][e], in log2 units
 
-  // K: product u, k-step j: granule (4j + kg) of slot slot_u0 + 4u (page p0 for rows 0-7, p1 for rows 8-15).
-  auto issue_k = [&](Frag (&kf)[2][4], int p0, int p1) {
-    const int pk = (n16 < 8) ? p0 : p1;
-    const size_t kb = ((size_t)pk * Hkv + hk) * (kD / 8 * kP) + (size_t)kg * kP + (slot_u0 & 15);
+  // K fragments of product u (row = slot slot_u0 + 4u of the step):
+  //   bf16: kf[u][j] = granule (4j + kg) of the row, j < 4 (page p0 for rows 0-7, p1 for rows 8-15);
+  //   fp8:  kf[u][0] = granule kg (dims 16kg..), kf[u][1] = granule kg + 4 (dims 64 + 16kg..) of page p0.
+  auto issue_k = [&](Frag (&kf)[2][kNK], int p0, int p1) {
+    if constexpr (kFp8) {
+      const size_t kb = ((size_t)p0 * Hkv + hk) * (kD / 16 * kP) + (size_t)kg * kP + slot_u0;
 #pragma unroll
-    for (int u = 0; u < 2; ++u)
+      for (int u = 0; u < 2; ++u)
 #pragma unroll
-      for (int j = 0; j < 4; ++j) kf[u][j].u = kpages[kb + (size_t)(4 * j) * kP + 4 * u];
+        for (int j = 0; j < 2; ++j) kf[u][j].u = kpages[kb + (size_t)(4 * j) * kP + 4 * u];
+    } else {
+      const int pk = (n16 < 8) ? p0 : p1;
+      const size_t kb = ((size_t)pk * Hkv + hk) * (kD / 8 * kP) + (size_t)kg * kP + (slot_u0 & 15);
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) kf[u][j].u = kpages[kb + (size_t)(4 * j) * kP + 4 * u];
+    }
   };
-  // V: column tile nt: dim 16nt + n16, slots 8*(kg&1).. of page kg/2.
-  auto issue_v = [&](Frag (&vf)[8], int p0, int p1) {
-    const int pv = (kg < 2) ? p0 : p1;
-    const size_t vb = (((size_t)pv * Hkv + hk) * kD + n16) * 2 + (kg & 1);
+  // V fragments, column tile nt = dim 16nt + n16: bf16: slots 8*(kg&1).. of page kg/2 (16 bytes);
+  // fp8: slots 8kg.. of the page (8 bytes).
+  auto issue_v = [&](VRaw (&vf)[8], int p0, int p1) {
+    if constexpr (kFp8) {
+      const size_t vb = (((size_t)p0 * Hkv + hk) * kD + n16) * 4 + kg;
 #pragma unroll
-    for (int nt = 0; nt < 8; ++nt) vf[nt].u = vpages[vb + (size_t)nt * 32];
+      for (int nt = 0; nt < 8; ++nt) vf[nt] = vpages[vb + (size_t)nt * 64];
+    } else {
+      const int pv = (kg < 2) ? p0 : p1;
+      const size_t vb = (((size_t)pv * Hkv + hk) * kD + n16) * 2 + (kg & 1);
+#pragma unroll
+      for (int nt = 0; nt < 8; ++nt) vf[nt] = vpages[vb + (size_t)nt * 32];
+    }
   };
 
   // One step: 32 slots starting at logical slot n0. `ragged` marks the request's last step when it reaches
-  // past kv_len L.
-  auto compute = [&](Frag (&kf)[2][4], Frag (&vf)[8], int n0, int L, bool ragged) {
+  // past kv_len L. ksc / vsc: the page's K and V scales (fp8; 1 for bf16).
+  auto compute = [&](Frag (&kf)[2][kNK], VRaw (&vf)[8], int n0, int L, bool ragged, float ksc, float vsc) {
     // Q' as the B operand of the QK products
     Frag bq[4];
 #pragma unroll
-    for (int jj = 0; jj < 2; ++jj)
+    for (int h = 0; h < 2; ++h)
 #pragma unroll
       for (int e = 0; e < 8; e += 2) {
-        bq[jj].w[e / 2] = pack_bf16x2(qlo[jj][e], qlo[jj][e + 1]);
-        bq[jj + 2].w[e / 2] = pack_bf16x2(qhi[jj][e], qhi[jj][e + 1]);
+        bq[h].w[e / 2] = pack_bf16x2(qlo[h][e], qlo[h][e + 1]);
+        bq[h + 2].w[e / 2] = pack_bf16x2(qhi[h][e], qhi[h][e + 1]);
       }
     // Rotate the K rows by their constant slot rotation and run the two QK products, then advance Q' by
     // R(-32). Six groups of four constants each; the constants of the next group are fetched from LDS while a
@@ -189,31 +228,44 @@ __global__ __launch_bounds__(64 * kWaves, kWgPerCu) void decode_mfma_bf16_kernel
           rc[(grp + 1) & 1][w] = (grp + 1 < 4) ? rotK[(grp + 1) * 4 + w][lane] : rotS[(grp + 1 - 4) * 4 + w][lane];
       }
       if (grp < 4) {
-        const int u = grp >> 1, jj = grp & 1;
-        if (jj == 0) sc[u] = floatx4{0.f, 0.f, 0.f, 0.f};
+        const int u = grp >> 1, h = grp & 1;
+        if (h == 0) sc[u] = floatx4{0.f, 0.f, 0.f, 0.f};
         Frag klo, khi;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          const uint32_t lo2 = kf[u][jj].w[w], hi2 = kf[u][jj + 2].w[w];
-          const float l0 = bf16_bits_to_f32(lo2 & 0xffffu), l1 = __uint_as_float(lo2 & 0xffff0000u);
-          const float h0 = bf16_bits_to_f32(hi2 & 0xffffu), h1 = __uint_as_float(hi2 & 0xffff0000u);
+        for (int w = 0; w < 4; ++w) {  // pairs 8h + 2w and 8h + 2w + 1
+          float l0, l1, h0, h1;
+          if constexpr (kFp8) {
+            const f32x2 lo = (w & 1) ? __builtin_amdgcn_cvt_pk_f32_fp8((int)kf[u][0].w[2 * h + (w >> 1)], true)
+                                     : __builtin_amdgcn_cvt_pk_f32_fp8((int)kf[u][0].w[2 * h + (w >> 1)], false);
+            const f32x2 hi = (w & 1) ? __builtin_amdgcn_cvt_pk_f32_fp8((int)kf[u][1].w[2 * h + (w >> 1)], true)
+                                     : __builtin_amdgcn_cvt_pk_f32_fp8((int)kf[u][1].w[2 * h + (w >> 1)], false);
+            l0 = lo[0]; l1 = lo[1]; h0 = hi[0]; h1 = hi[1];
+          } else {
+            const uint32_t lo2 = kf[u][h].w[w], hi2 = kf[u][h + 2].w[w];
+            l0 = bf16_bits_to_f32(lo2 & 0xffffu); l1 = __uint_as_float(lo2 & 0xffff0000u);
+            h0 = bf16_bits_to_f32(hi2 & 0xffffu); h1 = __uint_as_float(hi2 & 0xffff0000u);
+          }
           klo.w[w] = pack_bf16x2(l0 * r[w].x - h0 * r[w].y, l1 * r[w].z - h1 * r[w].w);  // r = {c0, s0, c1, s1}
           khi.w[w] = pack_bf16x2(h0 * r[w].x + l0 * r[w].y, h1 * r[w].z + l1 * r[w].w);
         }
-        sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(klo.v, bq[jj].v, sc[u], 0, 0, 0);
-        sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(khi.v, bq[jj + 2].v, sc[u], 0, 0, 0);
+        sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(klo.v, bq[h].v, sc[u], 0, 0, 0);
+        sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(khi.v, bq[h + 2].v, sc[u], 0, 0, 0);
       } else {
-        const int jj = grp - 4;
+        const int h = grp - 4;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-          const float a0 = qlo[jj][2 * w], b0 = qhi[jj][2 * w], a1 = qlo[jj][2 * w + 1], b1 = qhi[jj][2 * w + 1];
-          qlo[jj][2 * w] = a0 * r[w].x - b0 * r[w].y;
-          qhi[jj][2 * w] = b0 * r[w].x + a0 * r[w].y;
-          qlo[jj][2 * w + 1] = a1 * r[w].z - b1 * r[w].w;
-          qhi[jj][2 * w + 1] = b1 * r[w].z + a1 * r[w].w;
+          const float a0 = qlo[h][2 * w], b0 = qhi[h][2 * w], a1 = qlo[h][2 * w + 1], b1 = qhi[h][2 * w + 1];
+          qlo[h][2 * w] = a0 * r[w].x - b0 * r[w].y;
+          qhi[h][2 * w] = b0 * r[w].x + a0 * r[w].y;
+          qlo[h][2 * w + 1] = a1 * r[w].z - b1 * r[w].w;
+          qhi[h][2 * w + 1] = b1 * r[w].z + a1 * r[w].w;
         }
       }
       __builtin_amdgcn_sched_barrier(0);
+    }
+    if constexpr (kFp8) {
+      sc[0] *= ksc;
+      sc[1] *= ksc;
     }
     // lane (head n16, kg) now holds the scores of slots n0 + 8kg + 4u + e
     if (ragged) {
@@ -224,13 +276,26 @@ __global__ __launch_bounds__(64 * kWaves, kWgPerCu) void decode_mfma_bf16_kernel
           if (n0 + 8 * kg + 4 * u + e >= L) sc[u][e] = -INFINITY;
       // slots at or past kv_len may hold anything (even NaN): zero them in V
 #pragma unroll
-      for (int nt = 0; nt < 8; ++nt)
+      for (int nt = 0; nt < 8; ++nt) {
+        if constexpr (kFp8) {
+          uint32_t keep[2];
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          const int n = n0 + 8 * kg + 2 * w;
-          const uint32_t keep = (n < L ? 0x0000ffffu : 0u) | (n + 1 < L ? 0xffff0000u : 0u);
-          vf[nt].w[w] &= keep;
+          for (int w = 0; w < 2; ++w) {
+            keep[w] = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) keep[w] |= (n0 + 8 * kg + 4 * w + e < L) ? (0xffu << (8 * e)) : 0u;
+          }
+          vf[nt].x &= keep[0];
+          vf[nt].y &= keep[1];
+        } else {
+          uint32_t* vw = reinterpret_cast<uint32_t*>(&vf[nt]);
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            const int n = n0 + 8 * kg + 2 * w;
+            vw[w] &= (n < L ? 0x0000ffffu : 0u) | (n + 1 < L ? 0xffff0000u : 0u);
+          }
         }
+      }
     }
     const float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
                            fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
@@ -251,19 +316,53 @@ __global__ __launch_bounds__(64 * kWaves, kWgPerCu) void decode_mfma_bf16_kernel
       }
     }
     const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
-    Frag pa;
+    float pf[8];  // probabilities of slots n0 + 8kg + e', e' = 4u + e
     float psum = 0.f;
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
-      for (int e = 0; e < 4; e += 2) {
-        const float p0 = __builtin_amdgcn_exp2f(sc[u][e] - m_use), p1 = __builtin_amdgcn_exp2f(sc[u][e + 1] - m_use);
-        psum += p0 + p1;
-        pa.w[2 * u + e / 2] = pack_bf16x2(p0, p1);
+      for (int e = 0; e < 4; ++e) {
+        pf[4 * u + e] = __builtin_amdgcn_exp2f(sc[u][e] - m_use);
+        psum += pf[4 * u + e];
       }
     l_part += psum;
+    if constexpr (kFp8) {
+      // p * 4 = hi + lo, both e4m3 (p < 2^slack, so p * 4 < 448, the largest e4m3 value)
+      uint32_t hi[2], lo[2];
 #pragma unroll
-    for (int nt = 0; nt < 8; ++nt) o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa.v, vf[nt].v, o[nt], 0, 0, 0);
+      for (int w = 0; w < 2; ++w) {
+        float x[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[e] = pf[4 * w + e] * kPScaleFp8;
+        int hw = __builtin_amdgcn_cvt_pk_fp8_f32(x[0], x[1], 0, false);
+        hw = __builtin_amdgcn_cvt_pk_fp8_f32(x[2], x[3], hw, true);
+        const f32x2 b0 = __builtin_amdgcn_cvt_pk_f32_fp8(hw, false), b1 = __builtin_amdgcn_cvt_pk_f32_fp8(hw, true);
+        int lw = __builtin_amdgcn_cvt_pk_fp8_f32(x[0] - b0[0], x[1] - b0[1], 0, false);
+        lw = __builtin_amdgcn_cvt_pk_fp8_f32(x[2] - b1[0], x[3] - b1[1], lw, true);
+        hi[w] = (uint32_t)hw;
+        lo[w] = (uint32_t)lw;
+      }
+      const long a_hi = (long)(((uint64_t)hi[1] << 32) | hi[0]), a_lo = (long)(((uint64_t)lo[1] << 32) | lo[0]);
+      const float os = vsc * (1.f / kPScaleFp8);
+#pragma unroll
+      for (int nt = 0; nt < 8; ++nt) {
+        const long vb = (long)(((uint64_t)vf[nt].y << 32) | vf[nt].x);
+        floatx4 tmp = {0.f, 0.f, 0.f, 0.f};
+        tmp = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a_hi, vb, tmp, 0, 0, 0);
+        tmp = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a_lo, vb, tmp, 0, 0, 0);
+        o[nt] += tmp * os;
+      }
+    } else {
+      Frag pa;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) pa.w[w] = pack_bf16x2(pf[2 * w], pf[2 * w + 1]);
+#pragma unroll
+      for (int nt = 0; nt < 8; ++nt) {
+        Frag vb;
+        vb.u = vf[nt];
+        o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa.v, vb.v, o[nt], 0, 0, 0);
+      }
+    }
   };
 
   // ---- walk the wave's chunk request by request ----
@@ -285,21 +384,31 @@ __global__ __launch_bounds__(64 * kWaves, kWgPerCu) void decode_mfma_bf16_kernel
     }
     const int seg_end = min(pos_end, c1), n_st = seg_end - pos;
     const int L = sload(a.kv_lens, b), jend = (L + kP - 1) / kP;
-    const int j0 = 2 * (pos - c0);
+    const int j0 = kBps * (pos - c0);
     const bool ragged_end = (seg_end == c1) && (L & 31);
     const size_t bt_row = (size_t)b * a.max_blocks;
-    auto page = [&](int j) { return sload(a.block_tables, bt_row + min(j, jend - 1)); };
+    // page k of step st of this run (block index clamped to the request's last block)
+    auto page = [&](int st, int k) { return sload(a.block_tables, bt_row + min(j0 + kBps * st + k, jend - 1)); };
+    auto scale = [&](const float* tab, int pg) { return kFp8 ? sloadf(tab, pg) : 1.f; };
 
-    // q of head n16: the lane's four 8-element chunks (rows >= G are zeroed through the scale)
+    // q of head n16: the lane's four 8-element chunks (rows >= G are zeroed through the scale):
+    // qf[h] = pairs 8h.. low dims, qf[h + 2] = the same pairs' high dims (+64)
     Frag qf[4];
     {
-      const size_t qb = ((size_t)b * a.Hq + (size_t)hk * G + (n16 < G ? n16 : 0)) * (kD / 8) + kg;
+      const size_t qrow = ((size_t)b * a.Hq + (size_t)hk * G + (n16 < G ? n16 : 0)) * (kD / 8);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) qf[j].u = q4[qb + 4 * j];
+      for (int h = 0; h < 2; ++h) {
+        const int glo = kFp8 ? 2 * kg + h : 4 * h + kg;
+        qf[h].u = q4[qrow + glo];
+        qf[h + 2].u = q4[qrow + 8 + glo];
+      }
     }
-    Frag kA[2][4], kB[2][4], vf[8];
-    int pa0 = page(j0), pa1 = page(j0 + 1);      // pages of the step being computed
-    int pb0 = page(j0 + 2), pb1 = page(j0 + 3);  // pages of the step after it
+    Frag kA[2][kNK], kB[2][kNK];
+    VRaw vf[8];
+    int pa0 = page(0, 0), pa1 = page(0, kBps - 1);  // pages of the step being computed
+    int pb0 = page(1, 0), pb1 = page(1, kBps - 1);  // pages of the step after it
+    float ksa = scale(a.k_scales, pa0), vsa = scale(a.v_scales, pa0);
+    float ksb = scale(a.k_scales, pb0), vsb = scale(a.v_scales, pb0);
     issue_k(kA, pa0, pa1);
 
     // Q' = R(pos_q - n0) q, scaled into log2 units; reset the accumulators
@@ -311,17 +420,17 @@ __global__ __launch_bounds__(64 * kWaves, kWgPerCu) void decode_mfma_bf16_kernel
       const float delta = (float)(sload(a.q_positions, b) - j0 * kP);
       const float qs = n16 < G ? a.qk_scale_log2 : 0.f;
 #pragma unroll
-      for (int jj = 0; jj < 2; ++jj)
+      for (int h = 0; h < 2; ++h)
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          const int i = 32 * jj + 8 * kg + e;
-          const uint32_t wl = qf[jj].w[e >> 1], wh = qf[jj + 2].w[e >> 1];
+          const int i = freq_of(8 * h + e);
+          const uint32_t wl = qf[h].w[e >> 1], wh = qf[h + 2].w[e >> 1];
           const float x0 = qs * ((e & 1) ? __uint_as_float(wl & 0xffff0000u) : bf16_bits_to_f32(wl & 0xffffu));
           const float x1 = qs * ((e & 1) ? __uint_as_float(wh & 0xffff0000u) : bf16_bits_to_f32(wh & 0xffffu));
           const float t = turns_frac(delta, a.freq_hi[i], a.freq_lo[i]);
           const float c = __builtin_amdgcn_cosf(t), sn = __builtin_amdgcn_sinf(t);
-          qlo[jj][e] = x0 * c - x1 * sn;
-          qhi[jj][e] = x1 * c + x0 * sn;
+          qlo[h][e] = x0 * c - x1 * sn;
+          qhi[h][e] = x1 * c + x0 * sn;
         }
     }
 
@@ -329,15 +438,21 @@ __global__ __launch_bounds__(64 * kWaves, kWgPerCu) void decode_mfma_bf16_kernel
     for (int i = 0; i < n_st; i += 2) {
       issue_v(vf, pa0, pa1);
       if (i + 1 < n_st) issue_k(kB, pb0, pb1);
-      pa0 = page(j0 + 2 * i + 4);
-      pa1 = page(j0 + 2 * i + 5);
-      compute(kA, vf, (j0 + 2 * i) * kP, L, ragged_end && i == n_st - 1);
+      const float ks0 = ksa, vs0 = vsa;
+      pa0 = page(i + 2, 0);
+      pa1 = page(i + 2, kBps - 1);
+      ksa = scale(a.k_scales, pa0);
+      vsa = scale(a.v_scales, pa0);
+      compute(kA, vf, (j0 + kBps * i) * kP, L, ragged_end && i == n_st - 1, ks0, vs0);
       if (i + 1 >= n_st) break;
       issue_v(vf, pb0, pb1);
       if (i + 2 < n_st) issue_k(kA, pa0, pa1);
-      pb0 = page(j0 + 2 * i + 6);
-      pb1 = page(j0 + 2 * i + 7);
-      compute(kB, vf, (j0 + 2 * i + 2) * kP, L, ragged_end && i + 1 == n_st - 1);
+      const float ks1 = ksb, vs1 = vsb;
+      pb0 = page(i + 3, 0);
+      pb1 = page(i + 3, kBps - 1);
+      ksb = scale(a.k_scales, pb0);
+      vsb = scale(a.v_scales, pb0);
+      compute(kB, vf, (j0 + kBps * (i + 1)) * kP, L, ragged_end && i + 1 == n_st - 1, ks1, vs1);
     }
 
     // the partial of this (request, wave): un-normalised rows, reference max (log2 units), sum
@@ -400,23 +515,26 @@ int compute_units() {
 
 }  // namespace
 
-hipError_t launch_decode_mfma_bf16(const AttnArgs& a, hipStream_t s) {
+hipError_t launch_decode_mfma(const AttnArgs& a, hipStream_t s) {
   // kWgPerCu workgroups per compute unit, a whole number of them per KV head
   const int n_wg = max(kWgPerCu * compute_units() / a.Hkv, 1) * a.Hkv;
   const size_t lds = (size_t)(a.B + 1) * sizeof(int);
-  hipLaunchKernelGGL(decode_mfma_bf16_kernel, dim3(n_wg), dim3(64 * kWaves), lds, s, a);
+  if (a.kv_dtype == MEPIC_F8E4M3)
+    hipLaunchKernelGGL(decode_mfma_kernel<true>, dim3(n_wg), dim3(64 * kWaves), lds, s, a);
+  else
+    hipLaunchKernelGGL(decode_mfma_kernel<false>, dim3(n_wg), dim3(64 * kWaves), lds, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(combine_streamk_kernel, dim3(a.n_q * a.Hq), dim3(kD), 0, s, a);
   return hipGetLastError();
 }
 
-// Upper bound on the partials per request and the matching minimum chunk (in steps), from host-known sizes
-// only: with W waves per KV head and B requests a request needs about W/B pieces for an even cut; allow four
-// times that for skewed length mixes, never more than W.
+// Upper bound on the partials per request and the matching minimum chunk (in steps of 32 slots), from
+// host-known sizes only: with W waves per KV head and B requests a request needs about W/B pieces for an even
+// cut; allow four times that for skewed length mixes, never more than W.
 void decode_mfma_plan(int B, int Hkv, int max_kv_len, int* max_splits, int* min_chunk) {
   const int W = max(kWgPerCu * compute_units() / Hkv, 1) * kWaves;
-  const int max_steps = max(((max_kv_len + kP - 1) / kP + 1) / 2, 1);
+  const int max_steps = max((max_kv_len + 31) / 32, 1);
   int pieces = 4 * ((W + max(B, 1) - 1) / max(B, 1));
   if (pieces > W) pieces = W;
   if (pieces > max_steps) pieces = max_steps;

@@ -26,7 +26,7 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kD = 128, kP = 16;
-constexpr int kThreads = 512, kWavesPf = 8;
+constexpr int kThreads = 512;
 constexpr int kRows = 256;   // query rows per workgroup (32 per wave)
 constexpr int kTile = 64;    // KV slots per tile
 constexpr float kSlack = 6.f;
