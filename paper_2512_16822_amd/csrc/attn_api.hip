@@ -51,7 +51,7 @@ Plan make_plan(const mepic_attn_params* p, bool prefill) {
     // Matrix-core decode: persistent waves cut each KV head's sequence of steps into equal chunks; here only
     // the bound on partials per request (sizes the workspace) and the minimum chunk are fixed.
     pl.kernel = mfma_fp8 ? K_DECODE_MFMA_F8 : K_DECODE_MFMA_BF16;
-    decode_mfma_plan(p->B, p->Hkv, max_kv, &pl.n_splits, &pl.blocks_per_split);
+    decode_mfma_plan(p->B, p->Hkv, max_kv, mfma_fp8, &pl.n_splits, &pl.blocks_per_split);
     pl.workspace_bytes = (size_t)p->n_q_tokens * p->Hq * pl.n_splits * (p->D + 2) * sizeof(float) +
                          (size_t)(p->B + 2) * sizeof(int32_t);
     return pl;

@@ -68,6 +68,6 @@ hipError_t launch_combine(const AttnArgs& a, hipStream_t s);
 hipError_t launch_decode_mfma(const AttnArgs& a, hipStream_t s);  // bf16 or fp8 pages; includes its merge kernel
 hipError_t launch_prefill_mfma_bf16(const AttnArgs& a, hipStream_t s);  // n_splits = query tiles per request
 int prefill_mfma_rows_per_workgroup();
-void decode_mfma_plan(int B, int Hkv, int max_kv_len, int* max_splits, int* min_chunk);
+void decode_mfma_plan(int B, int Hkv, int max_kv_len, bool fp8, int* max_splits, int* min_chunk);
 
 }  // namespace mepic

@@ -17,7 +17,7 @@
 //   S^T[32 slots x 16 heads] = Khat[32 x 128] * Q'^T[128 x 16]     2 x 4 v_mfma_f32_16x16x32_bf16
 //   O  [16 heads x 128]     += P[16 x 32 slots] * V[32 x 128]      8     v_mfma_f32_16x16x32_bf16
 //
-// K of the next step and V of the current step are in flight while a step is computed.
+// K and V of the next step are in flight while a step is computed.
 //
 // Rotary embedding without per-key trigonometry: a key at position n0 + s (n0 = first slot of the
 // step) has  q^.k^ = (R(pos_q - n0) q) . (R(s) k).  R(s), s in [0, 32), is a per-lane constant (each
@@ -49,10 +49,21 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kD = 128;
 constexpr int kWaves = 4;             // waves per workgroup
-#ifndef MEPIC_DECODE_WG_PER_CU
-#define MEPIC_DECODE_WG_PER_CU 1
+// Workgroups resident per compute unit. bf16: one (a wave needs more than 256 registers for its two K/V
+// buffers; the kernel sits at the HBM limit anyway). fp8: two (half the bytes per slot make the kernel
+// compute-bound, its buffers are half as large, and the second wave per SIMD fills the issue slots the first
+// leaves while it waits on matrix-core and LDS results).
+#ifndef MEPIC_DECODE_WG_PER_CU_BF16
+#define MEPIC_DECODE_WG_PER_CU_BF16 1
 #endif
-constexpr int kWgPerCu = MEPIC_DECODE_WG_PER_CU;  // workgroups resident per compute unit
+#ifndef MEPIC_DECODE_WG_PER_CU_FP8
+#define MEPIC_DECODE_WG_PER_CU_FP8 2
+#endif
+constexpr int wg_per_cu(bool fp8) { return fp8 ? MEPIC_DECODE_WG_PER_CU_FP8 : MEPIC_DECODE_WG_PER_CU_BF16; }
+#ifndef MEPIC_DECODE_NBUF
+#define MEPIC_DECODE_NBUF 2
+#endif
+constexpr int kNBuf = MEPIC_DECODE_NBUF;          // register buffers of K and V per wave (prefetch depth + 1)
 constexpr float kRescaleSlack = 6.f;  // the running maximum may lag the true one by this much (log2 units)
 
 union Frag {  // one 16-byte operand fragment
@@ -100,7 +111,7 @@ __device__ __forceinline__ float sum_over_kgroups(float x) {
 constexpr float kPScaleFp8 = 4.f;     // probabilities (< 2^slack = 64) are multiplied by this before the e4m3 split
 
 template <bool kFp8>
-__global__ __launch_bounds__(64 * kWaves, kWgPerCu) void decode_mfma_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kernel(const AttnArgs a) {
   constexpr int kP = kFp8 ? 32 : 16;          // slots per page
   constexpr int kBps = kFp8 ? 1 : 2;          // blocks (pages) per step of 32 slots
   constexpr int kNK = kFp8 ? 2 : 4;           // 16-byte K fragments per lane and product
@@ -403,13 +414,30 @@ __global__ __launch_bounds__(64 * kWaves, kWgPerCu) void decode_mfma_kernel(cons
         qf[h + 2].u = q4[qrow + 8 + glo];
       }
     }
-    Frag kA[2][kNK], kB[2][kNK];
-    VRaw vf[8];
-    int pa0 = page(0, 0), pa1 = page(0, kBps - 1);  // pages of the step being computed
-    int pb0 = page(1, 0), pb1 = page(1, kBps - 1);  // pages of the step after it
-    float ksa = scale(a.k_scales, pa0), vsa = scale(a.v_scales, pa0);
-    float ksb = scale(a.k_scales, pb0), vsb = scale(a.v_scales, pb0);
-    issue_k(kA, pa0, pa1);
+    // Ring of kNBuf register buffers: while a step is computed the K and V of the next kNBuf-1 steps are in
+    // flight. Page ids and scales come through the scalar unit one iteration before they are needed.
+    Frag kbuf[kNBuf][2][kNK];
+    VRaw vbuf[kNBuf][8];
+    float ks_of[kNBuf], vs_of[kNBuf];
+    int nx0, nx1;
+    float nxk, nxv;
+    auto fetch = [&](int st) {
+      nx0 = page(st, 0);
+      nx1 = page(st, kBps - 1);
+      nxk = scale(a.k_scales, nx0);
+      nxv = scale(a.v_scales, nx0);
+    };
+#pragma unroll
+    for (int r = 0; r < kNBuf - 1; ++r) {
+      fetch(r);
+      ks_of[r] = nxk;
+      vs_of[r] = nxv;
+      if (r < n_st) {
+        issue_k(kbuf[r], nx0, nx1);
+        issue_v(vbuf[r], nx0, nx1);
+      }
+    }
+    fetch(kNBuf - 1);
 
     // Q' = R(pos_q - n0) q, scaled into log2 units; reset the accumulators
 #pragma unroll
@@ -434,25 +462,23 @@ __global__ __launch_bounds__(64 * kWaves, kWgPerCu) void decode_mfma_kernel(cons
         }
     }
 
-    // steps i and i+1 per iteration; K of the next step and V of this step are in flight during a step
-    for (int i = 0; i < n_st; i += 2) {
-      issue_v(vf, pa0, pa1);
-      if (i + 1 < n_st) issue_k(kB, pb0, pb1);
-      const float ks0 = ksa, vs0 = vsa;
-      pa0 = page(i + 2, 0);
-      pa1 = page(i + 2, kBps - 1);
-      ksa = scale(a.k_scales, pa0);
-      vsa = scale(a.v_scales, pa0);
-      compute(kA, vf, (j0 + kBps * i) * kP, L, ragged_end && i == n_st - 1, ks0, vs0);
-      if (i + 1 >= n_st) break;
-      issue_v(vf, pb0, pb1);
-      if (i + 2 < n_st) issue_k(kA, pa0, pa1);
-      const float ks1 = ksb, vs1 = vsb;
-      pb0 = page(i + 3, 0);
-      pb1 = page(i + 3, kBps - 1);
-      ksb = scale(a.k_scales, pb0);
-      vsb = scale(a.v_scales, pb0);
-      compute(kB, vf, (j0 + kBps * (i + 1)) * kP, L, ragged_end && i + 1 == n_st - 1, ks1, vs1);
+    for (int s0 = 0; s0 < n_st; s0 += kNBuf) {
+#pragma unroll
+      for (int r = 0; r < kNBuf; ++r) {
+        const int st = s0 + r;
+        if (st < n_st) {
+          constexpr int kLead = kNBuf - 1;
+          const int rn = (r + kLead) % kNBuf;  // buffer of step st + kLead (free: step st - 1 used it)
+          ks_of[rn] = nxk;
+          vs_of[rn] = nxv;
+          if (st + kLead < n_st) {
+            issue_k(kbuf[rn], nx0, nx1);
+            issue_v(vbuf[rn], nx0, nx1);
+          }
+          fetch(st + kNBuf);
+          compute(kbuf[r], vbuf[r], (j0 + kBps * st) * kP, L, ragged_end && st == n_st - 1, ks_of[r], vs_of[r]);
+        }
+      }
     }
 
     // the partial of this (request, wave): un-normalised rows, reference max (log2 units), sum
@@ -516,10 +542,11 @@ int compute_units() {
 }  // namespace
 
 hipError_t launch_decode_mfma(const AttnArgs& a, hipStream_t s) {
-  // kWgPerCu workgroups per compute unit, a whole number of them per KV head
-  const int n_wg = max(kWgPerCu * compute_units() / a.Hkv, 1) * a.Hkv;
+  // a fixed number of workgroups per compute unit, a whole number of them per KV head
+  const bool fp8 = a.kv_dtype == MEPIC_F8E4M3;
+  const int n_wg = max(wg_per_cu(fp8) * compute_units() / a.Hkv, 1) * a.Hkv;
   const size_t lds = (size_t)(a.B + 1) * sizeof(int);
-  if (a.kv_dtype == MEPIC_F8E4M3)
+  if (fp8)
     hipLaunchKernelGGL(decode_mfma_kernel<true>, dim3(n_wg), dim3(64 * kWaves), lds, s, a);
   else
     hipLaunchKernelGGL(decode_mfma_kernel<false>, dim3(n_wg), dim3(64 * kWaves), lds, s, a);
@@ -532,8 +559,8 @@ hipError_t launch_decode_mfma(const AttnArgs& a, hipStream_t s) {
 // Upper bound on the partials per request and the matching minimum chunk (in steps of 32 slots), from
 // host-known sizes only: with W waves per KV head and B requests a request needs about W/B pieces for an even
 // cut; allow four times that for skewed length mixes, never more than W.
-void decode_mfma_plan(int B, int Hkv, int max_kv_len, int* max_splits, int* min_chunk) {
-  const int W = max(kWgPerCu * compute_units() / Hkv, 1) * kWaves;
+void decode_mfma_plan(int B, int Hkv, int max_kv_len, bool fp8, int* max_splits, int* min_chunk) {
+  const int W = max(wg_per_cu(fp8) * compute_units() / Hkv, 1) * kWaves;
   const int max_steps = max((max_kv_len + 31) / 32, 1);
   int pieces = 4 * ((W + max(B, 1) - 1) / max(B, 1));
   if (pieces > W) pieces = W;
