@@ -28,6 +28,13 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# command (counter readings in KiB, each scaled by what the same counter reads for a 1 GiB device copy:
+# FETCH_SIZE x2.000, WRITE_SIZE x1.000). Summaries with the commands are under profiles/.
+MEASURED_TRAFFIC = {
+    ("cfg2_llama3_8b_decode_bf16", "duplicated", "decode_mfma_bf16"): int((552122.3 * 2.0 + 3221.6) * 1024),
+}
+
 
 def algorithmic_bytes(case) -> int:
     """Bytes the method must move per call: K and V of every addressed slot, block-table entries,
@@ -55,21 +62,29 @@ def visible_pairs(case) -> int:
 
 
 def time_steps(dc, steps: int, warmup: int):
-    """Run warmup + steps calls on torch's current stream; HIP events bracket the timed region and every
-    single step. Returns (total ms, list of per-step ms)."""
+    """Run warmup + steps calls on torch's current stream. HIP events bracket the timed region and every
+    single step (torch events on the stream the library launches on); a second set of HIP events, handed to
+    the library through timing_start / timing_stop, brackets the main kernel of every call alone.
+    Returns (total ms, list of per-step ms, list of per-step main-kernel ms)."""
     import torch
-    run = dc.M.attn_prefill if dc.prefill else dc.M.attn_decode
+    M = dc.M
+    run = M.attn_prefill if dc.prefill else M.attn_decode
     for _ in range(warmup):
         run(dc.params)
     torch.cuda.synchronize()
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    k0 = [M.HipEvent() for _ in range(steps)]
+    k1 = [M.HipEvent() for _ in range(steps)]
     ev[0].record()
     for i in range(steps):
+        dc.params.timing_start, dc.params.timing_stop = k0[i].handle, k1[i].handle
         run(dc.params)
         ev[i + 1].record()
     torch.cuda.synchronize()
+    dc.params.timing_start = dc.params.timing_stop = None
     per = [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]
-    return ev[0].elapsed_time(ev[steps]), per
+    kern = [k0[i].elapsed_ms(k1[i]) for i in range(steps)]
+    return ev[0].elapsed_time(ev[steps]), per, kern
 
 
 def main() -> int:
@@ -81,6 +96,9 @@ def main() -> int:
     ap.add_argument("--layout", default="both", choices=["both", "shared", "duplicated"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=0, help="oracle sample size in (token, head) rows")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain 1 GiB device copy three times (calibrates the FETCH_SIZE / WRITE_SIZE "
+                         "counters of a rocprofv3 --pmc run of this same command)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -97,6 +115,15 @@ def main() -> int:
     M.load()
     st = W.config(args.config)
 
+    if args.copy_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
+
     # ---- scheduling path (host): align every request, report the accounting ----
     t0 = time.perf_counter()
     aligned, pool = align_with_library(M, st)
@@ -110,8 +137,9 @@ def main() -> int:
     for layout in layouts:
         c = case if layout == "shared" else W.to_duplicated(case)
         dc = DeviceCase(M, c)
-        total_ms, per = time_steps(dc, args.steps, args.warmup)
+        total_ms, per, kern = time_steps(dc, args.steps, args.warmup)
         results[layout] = dict(ms=total_ms / args.steps, min_ms=min(per), kernel=M.last_kernel(),
+                               kernel_ms=sum(kern) / len(kern),
                                pages=c.pages.num_pages, out=dc.out.float().cpu())
         del dc
         torch.cuda.empty_cache()
@@ -125,17 +153,19 @@ def main() -> int:
     ms = results[main_layout]["ms"]
     if prefill:
         value, unit, metric = flops / (ms * 1e-3) / 1e12, "TFLOP/s", "fused-RoPE paged prefill attention throughput"
-        rms = results[roof_layout]["ms"]
+        rms = results[roof_layout]["kernel_ms"]
         ach = flops / (rms * 1e-3) / 1e12
         roofline = dict(bound="mfma", achieved=ach, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
                         frac=ach / MFMA_BF16_PEAK_TFLOPS, traffic=None, layout=roof_layout,
-                        kernel=results[roof_layout]["kernel"], kernel_ms=rms)
+                        kernel=results[roof_layout]["kernel"], kernel_ms=rms, call_ms=results[roof_layout]["ms"])
     else:
         value, unit, metric = abytes / (ms * 1e-3) / 1e9, "GB/s", "fused-RoPE paged decode attention KV throughput"
-        rms = results[roof_layout]["ms"]
+        rms = results[roof_layout]["kernel_ms"]
         ach = abytes / (rms * 1e-3) / 1e9
+        traffic = MEASURED_TRAFFIC.get((st.name, roof_layout, results[roof_layout]["kernel"]))
         roofline = dict(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS,
-                        traffic=None, layout=roof_layout, kernel=results[roof_layout]["kernel"], kernel_ms=rms)
+                        traffic=traffic, layout=roof_layout, kernel=results[roof_layout]["kernel"], kernel_ms=rms,
+                        call_ms=results[roof_layout]["ms"])
 
     # ---- the oracle on this machine's host cores, on a bounded sample of the same workload ----
     cpu = None
@@ -171,7 +201,8 @@ def main() -> int:
                             kv_len_mean=float(case.kv_lens.mean()), kv_len_max=int(case.kv_lens.max()),
                             n_q_tokens=case.n_q, algorithmic_bytes=abytes, useful_flops=flops),
                 roofline=roofline, cpu_baseline=cpu,
-                layouts={k: dict(ms_per_step=v["ms"], min_ms=v["min_ms"], pages=v["pages"], kernel=v["kernel"],
+                layouts={k: dict(ms_per_step=v["ms"], min_ms=v["min_ms"], kernel_ms=v["kernel_ms"], pages=v["pages"],
+                                 kernel=v["kernel"],
                                  gbs=abytes / (v["ms"] * 1e-3) / 1e9) for k, v in results.items()},
                 accounting=dict(pages_unique=stats["pages_in_use_unique"],
                                 pages_duplicated=stats["pages_logical_duplicated"],

@@ -195,6 +195,9 @@ typedef struct {
   uint32_t flags;                   /* MEPIC_FLAG_*                                                   */
   void* workspace;                  /* device scratch for split-K partials, 256-byte aligned          */
   size_t workspace_bytes;
+  void* timing_start;               /* optional hipEvent_t pair (both or neither): recorded on the stream     */
+  void* timing_stop;                /*   right before / after the call's main kernel, i.e. without the small  */
+                                    /*   merge kernel that follows it in decode. A profiling aid; NULL = off.  */
 } mepic_attn_params;
 
 /* Bytes of workspace mepic_attn_decode / mepic_attn_prefill need for these shapes (only the shape,

@@ -61,7 +61,8 @@ class AttnParams(ctypes.Structure):
                 + [(n, ctypes.c_int32) for n in ("B", "n_q_tokens", "Hq", "Hkv", "D", "P", "max_blocks", "num_pages",
                                                  "max_kv_len", "max_q_len", "q_dtype", "kv_dtype")]
                 + [("rope_theta", ctypes.c_float), ("sm_scale", ctypes.c_float), ("flags", ctypes.c_uint32),
-                   ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)])
+                   ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+                   ("timing_start", ctypes.c_void_p), ("timing_stop", ctypes.c_void_p)])
 
 
 _lib = None
@@ -242,3 +243,46 @@ def attn_prefill(params: AttnParams, stream=None) -> None:
     rc = load().mepic_attn_prefill(ctypes.byref(params), _stream_handle(stream))
     if rc != OK:
         raise MepicError(rc, "mepic_attn_prefill")
+
+
+# ------------------------------------------------------------------------------------------------
+# HIP events for mepic_attn_params.timing_start / timing_stop (plain runtime calls, nothing computed)
+# ------------------------------------------------------------------------------------------------
+_hip = None
+
+
+def _hiprt() -> ctypes.CDLL:
+    global _hip
+    if _hip is None:
+        _hip = ctypes.CDLL("libamdhip64.so")
+        _hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        _hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        _hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        _hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+    return _hip
+
+
+class HipEvent:
+    """A hipEvent_t whose handle can be put into AttnParams.timing_start / timing_stop."""
+
+    def __init__(self):
+        self.handle = ctypes.c_void_p()
+        if _hiprt().hipEventCreate(ctypes.byref(self.handle)) != 0:
+            raise RuntimeError("hipEventCreate failed")
+
+    def __del__(self):
+        try:
+            if self.handle:
+                _hiprt().hipEventDestroy(self.handle)
+        except Exception:
+            pass
+
+    def synchronize(self) -> None:
+        if _hiprt().hipEventSynchronize(self.handle) != 0:
+            raise RuntimeError("hipEventSynchronize failed")
+
+    def elapsed_ms(self, later: "HipEvent") -> float:
+        ms = ctypes.c_float()
+        if _hiprt().hipEventElapsedTime(ctypes.byref(ms), self.handle, later.handle) != 0:
+            raise RuntimeError("hipEventElapsedTime failed")
+        return float(ms.value)

@@ -88,6 +88,10 @@ Plan make_plan(const mepic_attn_params* p, bool prefill) {
   return pl;
 }
 
+void mark(void* ev, hipStream_t s) {
+  if (ev) (void)hipEventRecord(reinterpret_cast<hipEvent_t>(ev), s);
+}
+
 int run(const mepic_attn_params* p, void* hip_stream, bool prefill) {
   const int rc = check_shapes(p, prefill);
   if (rc != MEPIC_OK) return rc;
@@ -97,12 +101,14 @@ int run(const mepic_attn_params* p, void* hip_stream, bool prefill) {
   if (prefill && !p->cu_q_lens) return MEPIC_ERR_INVALID;
   if (p->kv_dtype == MEPIC_F8E4M3 && (!p->k_scales || !p->v_scales)) return MEPIC_ERR_INVALID;
   if (!(p->rope_theta > 0.f)) return MEPIC_ERR_INVALID;
+  if ((p->timing_start == nullptr) != (p->timing_stop == nullptr)) return MEPIC_ERR_INVALID;
 
   const Plan pl = make_plan(p, prefill);
   if (pl.workspace_bytes && (!p->workspace || p->workspace_bytes < pl.workspace_bytes)) return MEPIC_ERR_CAPACITY;
   if (reinterpret_cast<uintptr_t>(p->workspace) & 255u) return MEPIC_ERR_INVALID;
 
   AttnArgs a{};
+  a.timing_start = p->timing_start; a.timing_stop = p->timing_stop;
   a.q = p->q; a.out = p->out; a.k_pages = p->k_pages; a.v_pages = p->v_pages;
   a.k_scales = p->k_scales; a.v_scales = p->v_scales;
   a.block_tables = p->block_tables; a.kv_lens = p->kv_lens; a.q_positions = p->q_positions;
@@ -137,11 +143,15 @@ int run(const mepic_attn_params* p, void* hip_stream, bool prefill) {
       break;
     case K_PREFILL_MFMA_BF16:
       g_last_kernel = "prefill_mfma_bf16";
+      mark(a.timing_start, s);
       e = launch_prefill_mfma_bf16(a, s);
+      mark(a.timing_stop, s);
       break;
     default:
       g_last_kernel = "general";
+      mark(a.timing_start, s);
       e = launch_general(a, s);
+      mark(a.timing_stop, s);
       if (e == hipSuccess) e = launch_combine(a, s);
       break;
   }

@@ -27,6 +27,8 @@ struct AttnArgs {
   const uint32_t* block_valid_mask;  // nullable
   float* part_o;                     // [n_q][Hq][n_splits][D] un-normalised partial outputs
   float* part_ml;                    // [n_q][Hq][n_splits][2] running max (log2 units) and sum
+  void* timing_start;                // optional hipEvent_t pair around the main kernel
+  void* timing_stop;
   int32_t* part_meta;                // stream-K decode: steps before each request [B+1], then the chunk
   int32_t B, n_q, Hq, Hkv, D, P, max_blocks, num_pages, G;
   int32_t q_dtype, kv_dtype;

@@ -546,11 +546,13 @@ hipError_t launch_decode_mfma(const AttnArgs& a, hipStream_t s) {
   const bool fp8 = a.kv_dtype == MEPIC_F8E4M3;
   const int n_wg = max(wg_per_cu(fp8) * compute_units() / a.Hkv, 1) * a.Hkv;
   const size_t lds = (size_t)(a.B + 1) * sizeof(int);
+  if (a.timing_start) (void)hipEventRecord(reinterpret_cast<hipEvent_t>(a.timing_start), s);
   if (fp8)
     hipLaunchKernelGGL(decode_mfma_kernel<true>, dim3(n_wg), dim3(64 * kWaves), lds, s, a);
   else
     hipLaunchKernelGGL(decode_mfma_kernel<false>, dim3(n_wg), dim3(64 * kWaves), lds, s, a);
   hipError_t e = hipGetLastError();
+  if (a.timing_stop) (void)hipEventRecord(reinterpret_cast<hipEvent_t>(a.timing_stop), s);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(combine_streamk_kernel, dim3(a.n_q * a.Hq), dim3(kD), 0, s, a);
   return hipGetLastError();
