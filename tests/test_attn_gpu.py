@@ -196,3 +196,65 @@ def test_full_size_decode_configs_sampled(mepic, oracle_attn, cfg, n_rows):
 def test_full_size_prefill_config3_sampled(mepic, oracle_attn):
     case = build_case(mepic, W.config(3))
     check(mepic, oracle_attn, case, rows=sample_rows(case, 48))
+
+
+# ------------------------------------------------------------------ more shapes for the matrix-core paths
+@pytest.mark.parametrize("kv_dtype,P,kernel", [("bf16", 16, "decode_mfma_bf16"), ("f8e4m3", 32, "decode_mfma_fp8")])
+@pytest.mark.parametrize("G", [1, 2, 8, 16])
+def test_decode_matrix_core_group_sizes(mepic, oracle_attn, kv_dtype, P, kernel, G):
+    st = small_decode(kv_dtype, seed=31 + G, P=P, B=6, Hq=2 * G, Hkv=2, n_chunks=(1, 6), chunk_tokens=192, question=21)
+    check(mepic, oracle_attn, build_case(mepic, st), expect_kernel=kernel)
+
+
+@pytest.mark.parametrize("kv_dtype,P", [("bf16", 16), ("f8e4m3", 32)])
+def test_decode_many_requests_skewed_lengths(mepic, oracle_attn, kv_dtype, P):
+    """More requests than one wave scans at once, one very long request among short and empty ones: the
+    equal-chunk cut crosses many request boundaries and the long request is cut into many pieces."""
+    st = W.Structure("skewed", "decode", 150, 8, 2, 128, P, 5e5, "bf16", kv_dtype, 37)
+    rng = np.random.default_rng(37)
+    C = W.CHUNK_KEY_BASE
+    for b in range(st.B):
+        if b == 77:
+            segs = [(1, 4096, C + 1)] * 6 + [(0, 333, 0)]
+        else:
+            segs = [(0, int(rng.integers(1, 90)), 0)]
+            if rng.random() < 0.3:
+                segs.insert(0, (1, 256, C + 2))
+        st.requests.append(segs)
+        st.n_q.append(1)
+    case = build_case(mepic, st)
+    case.kv_lens[[3, 40, 149]] = 0                        # empty requests in between
+    rows = [(b, h) for b in (0, 3, 40, 76, 77, 78, 148, 149) for h in range(8)]
+    err, dc = check(mepic, oracle_attn, case, rows=rows)
+    assert mepic.last_kernel().startswith("decode_mfma")
+    out = dc.out.float()
+    assert torch.isfinite(out).all() and (out[[3, 40, 149]] == 0).all()
+
+
+def test_dispatch_names(mepic, oracle_attn):
+    """Which kernel serves which case (the general kernel must stay reachable for everything else)."""
+    for st, want in ((small_decode("bf16"), "decode_mfma_bf16"), (small_decode("f8e4m3", P=32), "decode_mfma_fp8"),
+                     (small_decode("f32"), "general"), (small_decode("bf16", P=32), "general"),
+                     (small_decode("f8e4m3", P=16), "general"), (small_decode("bf16", D=64), "general")):
+        check(mepic, oracle_attn, build_case(mepic, st), expect_kernel=want)
+
+
+@pytest.mark.parametrize("G", [1, 2, 8])
+def test_prefill_matrix_core_group_sizes_and_ragged_kv(mepic, oracle_attn, G):
+    """kv_len not a multiple of the 64-slot tile, query counts not a multiple of the row tile."""
+    st = W.prefill_structure("prefill_g", 41 + G, B=3, Hq=2 * G, Hkv=2, D=128, P=16, theta=5e5, n_chunks=3,
+                             chunk_tokens=208, pool=3, q_tokens=1, max_gap_pages=1)
+    st.n_q = [37, 300, 5]
+    for b, n in enumerate(st.n_q):
+        st.requests[b][-1] = (0, n + 11 * b, 0)
+    check(mepic, oracle_attn, build_case(mepic, st), expect_kernel="prefill_mfma_bf16")
+
+
+def test_prefill_queries_in_the_middle_and_far_positions(mepic, oracle_attn):
+    """Query positions well inside the context (most of the KV is causally hidden) and positions around 40K."""
+    st = W.prefill_structure("prefill_mid", 43, B=2, Hq=8, Hkv=2, D=128, P=16, theta=5e5, n_chunks=40,
+                             chunk_tokens=1024, pool=4, q_tokens=40, max_gap_pages=0)
+    case = build_case(mepic, st)
+    case.q_positions[:40] = np.arange(1000, 1040)         # request 0: sees only the first ~1000 slots
+    rows = [(t, h) for t in (0, 17, 39, 40, 61, 79) for h in (0, 3, 7)]
+    check(mepic, oracle_attn, case, rows=rows, expect_kernel="prefill_mfma_bf16")
