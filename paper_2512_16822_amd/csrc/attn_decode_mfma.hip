@@ -398,9 +398,21 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
     const int j0 = kBps * (pos - c0);
     const bool ragged_end = (seg_end == c1) && (L & 31);
     const size_t bt_row = (size_t)b * a.max_blocks;
-    // page k of step st of this run (block index clamped to the request's last block)
-    auto page = [&](int st, int k) { return sload(a.block_tables, bt_row + min(j0 + kBps * st + k, jend - 1)); };
-    auto scale = [&](const float* tab, int pg) { return kFp8 ? sloadf(tab, pg) : 1.f; };
+    // Page ids of the run: lane i of bt_cur holds the page of block j0 + 64*bt_win + i (clamped to the
+    // request's last block), bt_nxt the 64 after those; a step reads its ids with v_readlane. Vector loads on
+    // purpose: scalar loads share a counter with the LDS reads, so every wait for a rotation constant would
+    // also wait for them. The next window is fetched a whole window ahead.
+    auto bt_load = [&](int win) { return a.block_tables[bt_row + min(j0 + 64 * win + lane, jend - 1)]; };
+    int bt_win = 0, bt_cur = bt_load(0), bt_nxt = bt_load(1);
+    auto page = [&](int st, int k) {  // page k of step st; called with non-decreasing st
+      const int rel = kBps * st + k;
+      if ((rel >> 6) != bt_win) {
+        ++bt_win;
+        bt_cur = bt_nxt;
+        bt_nxt = bt_load(bt_win + 1);
+      }
+      return __builtin_amdgcn_readlane(bt_cur, rel & 63);
+    };
 
     // q of head n16: the lane's four 8-element chunks (rows >= G are zeroed through the scale):
     // qf[h] = pairs 8h.. low dims, qf[h + 2] = the same pairs' high dims (+64)
@@ -415,29 +427,24 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
       }
     }
     // Ring of kNBuf register buffers: while a step is computed the K and V of the next kNBuf-1 steps are in
-    // flight. Page ids and scales come through the scalar unit one iteration before they are needed.
+    // flight.
     Frag kbuf[kNBuf][2][kNK];
     VRaw vbuf[kNBuf][8];
-    float ks_of[kNBuf], vs_of[kNBuf];
-    int nx0, nx1;
-    float nxk, nxv;
-    auto fetch = [&](int st) {
-      nx0 = page(st, 0);
-      nx1 = page(st, kBps - 1);
-      nxk = scale(a.k_scales, nx0);
-      nxv = scale(a.v_scales, nx0);
+    float ks_of[kNBuf], vs_of[kNBuf];  // page scales (fp8), loaded with the step's K and V
+    auto issue_step = [&](int rb, int st) {
+      const int p0 = page(st, 0), p1 = kBps > 1 ? page(st, kBps - 1) : p0;
+      if constexpr (kFp8) {
+        ks_of[rb] = a.k_scales[p0];
+        vs_of[rb] = a.v_scales[p0];
+      } else {
+        ks_of[rb] = vs_of[rb] = 1.f;
+      }
+      issue_k(kbuf[rb], p0, p1);
+      issue_v(vbuf[rb], p0, p1);
     };
 #pragma unroll
-    for (int r = 0; r < kNBuf - 1; ++r) {
-      fetch(r);
-      ks_of[r] = nxk;
-      vs_of[r] = nxv;
-      if (r < n_st) {
-        issue_k(kbuf[r], nx0, nx1);
-        issue_v(vbuf[r], nx0, nx1);
-      }
-    }
-    fetch(kNBuf - 1);
+    for (int r = 0; r < kNBuf - 1; ++r)
+      if (r < n_st) issue_step(r, r);
 
     // Q' = R(pos_q - n0) q, scaled into log2 units; reset the accumulators
 #pragma unroll
@@ -469,13 +476,7 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
         if (st < n_st) {
           constexpr int kLead = kNBuf - 1;
           const int rn = (r + kLead) % kNBuf;  // buffer of step st + kLead (free: step st - 1 used it)
-          ks_of[rn] = nxk;
-          vs_of[rn] = nxv;
-          if (st + kLead < n_st) {
-            issue_k(kbuf[rn], nx0, nx1);
-            issue_v(vbuf[rn], nx0, nx1);
-          }
-          fetch(st + kNBuf);
+          if (st + kLead < n_st) issue_step(rn, st + kLead);
           compute(kbuf[r], vbuf[r], (j0 + kBps * st) * kP, L, ragged_end && st == n_st - 1, ks_of[r], vs_of[r]);
         }
       }
