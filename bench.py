@@ -87,6 +87,60 @@ def time_steps(dc, steps: int, warmup: int):
     return ev[0].elapsed_time(ev[steps]), per, kern
 
 
+def bench_commit(args) -> int:
+    """`--commit`: the commit step alone (scatter of new un-rotated K/V into their pages) on the prompt-commit
+    workload: 64 requests x 1024 new tokens of Llama-3-8B KV shape (Hkv 8, D 128), bf16 pages of 16 slots
+    (`--commit fp8`: e4m3 pages of 32 slots). One JSON line, HBM roofline on source bytes read + page bytes
+    written."""
+    import numpy as np
+    import torch
+    import paper_2512_16822_amd as M
+    import workloads as W
+    M.load()
+    fp8 = args.commit == "fp8"
+    kv_dtype, P = ("f8e4m3", 32) if fp8 else ("bf16", 16)
+    Hkv, D, B, T = 8, 128, 64, 1024
+    MB = T // P + 1
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(10)
+    pages = W.gen_pages(25, B * MB, Hkv, P, D, kv_dtype)
+    bt = rng.permutation(B * MB).reshape(B, MB).astype(np.int32)
+    i32 = lambda a: torch.tensor(np.asarray(a, dtype=np.int32), dtype=torch.int32, device=dev)
+    src = lambda: torch.from_numpy(rng.standard_normal((B * T, Hkv, D)).astype(np.float32)).to(torch.bfloat16).to(dev)
+    k_new, v_new = src(), src()
+    k_dev, v_dev = pages.k.to(dev), pages.v.to(dev)
+    ks = None if pages.k_scales is None else pages.k_scales.to(dev)
+    vs = None if pages.v_scales is None else pages.v_scales.to(dev)
+    p = M.make_commit_params(k_new, v_new, k_dev, v_dev, i32(bt), i32(np.arange(B)), i32([(b % 3) * 8 for b in range(B)]),
+                             i32(np.arange(B + 1) * T), k_scales=ks, v_scales=vs)
+    for _ in range(args.warmup):
+        M.kv_commit(p)
+    torch.cuda.synchronize()
+    k0 = [M.HipEvent() for _ in range(args.steps)]
+    k1 = [M.HipEvent() for _ in range(args.steps)]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(args.steps):
+        p.timing_start, p.timing_stop = k0[i].handle, k1[i].handle
+        M.kv_commit(p)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    kern_ms = sum(a.elapsed_ms(b) for a, b in zip(k0, k1)) / args.steps
+    n_el = 2 * B * T * Hkv * D
+    abytes = n_el * 2 + n_el * (1 if fp8 else 2) + B * MB * 4 + (B * MB * 8 if fp8 else 0) + (3 * B + 1) * 4
+    ach = abytes / (kern_ms * 1e-3) / 1e9
+    print(json.dumps(dict(metric="KV commit throughput (source read + page write)", value=abytes / (ms * 1e-3) / 1e9,
+                          unit="GB/s", n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms,
+                          higher_is_better=True, scaling="weak", vs_baseline=None,
+                          dtype="bf16 -> e4m3" if fp8 else "bf16", data="synthetic",
+                          config=dict(workload=f"prompt_commit_64x1024_llama3_8b_{kv_dtype}", B=B, new_tokens=B * T,
+                                      Hkv=Hkv, D=D, P=P, algorithmic_bytes=abytes),
+                          roofline=dict(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS,
+                                        traffic=None, kernel="kv_commit", kernel_ms=kern_ms), cpu_baseline=None)))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -99,11 +153,16 @@ def main() -> int:
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 1 GiB device copy three times (calibrates the FETCH_SIZE / WRITE_SIZE "
                          "counters of a rocprofv3 --pmc run of this same command)")
+    ap.add_argument("--commit", nargs="?", const="bf16", default=None, choices=["bf16", "fp8"],
+                    help="benchmark the commit step (mepic_kv_commit) instead of attention")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
         return 2
+
+    if args.commit:
+        return bench_commit(args)
 
     import numpy as np
     import torch

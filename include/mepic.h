@@ -216,6 +216,50 @@ int mepic_attn_prefill(const mepic_attn_params* params, void* hip_stream);
  * "" before any call). For tests and reports. */
 const char* mepic_last_kernel(void);
 
+/* ------------------------------------------------------------------------------------------------
+ * Commit to paged KV (§3.3.2): the K and V vectors just computed for new tokens (prompt tokens, the
+ * recomputed first block of a cached chunk, a newly seen chunk, the token a decode step produced) are
+ * written straight into the pages the aligner assigned, WITHOUT positional encoding, in the page layout
+ * above. The token-to-page mapping is the block table itself; nothing else is translated.
+ *
+ * New tokens arrive packed, [n_tokens][Hkv][D], as a list of runs: run r holds the tokens
+ * cu_run_tokens[r] .. cu_run_tokens[r+1]-1, which occupy the consecutive logical slots
+ * run_first_slot[r], run_first_slot[r]+1, ... of request run_request[r] (logical slot n -> page
+ * block_tables[request][n / P], slot n % P). A decode step is B runs of one token. Slots no run names
+ * keep their contents. Two runs (in one call, or in calls that overlap on the GPU) that name the same
+ * slot race.
+ *
+ * dtypes: (src F32 -> pages F32), (BF16 -> BF16): a copy; (BF16 -> F8E4M3): quantised with the
+ * destination page's scale, which the caller supplies (the paper names no low-precision format):
+ * code = e4m3fn value nearest to fp32(x) / scale (one fp32 division), ties to even, magnitudes beyond
+ * 448 saturate, the sign is kept. Scales are read, never written.
+ *
+ * A token whose request index, block index or page id is out of range is skipped (nothing is written
+ * for it); the host checks only shapes and null pointers. Asynchronous on the stream; allocates
+ * nothing; needs no workspace.
+ * Errors: MEPIC_ERR_INVALID (null pointers, negative sizes, one timing event without the other),
+ * MEPIC_ERR_UNSUPPORTED (dtype pair, D not 64/128, P not 16/32), MEPIC_ERR_LAUNCH.
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct {
+  const void* k_new;               /* device [n_tokens][Hkv][D], src_dtype, UN-rotated                */
+  const void* v_new;               /* device [n_tokens][Hkv][D], src_dtype                            */
+  void* k_pages;                   /* device, K page layout, kv_dtype (written)                       */
+  void* v_pages;                   /* device, V page layout, kv_dtype (written)                       */
+  const float* k_scales;           /* device [num_pages] fp32 > 0; required iff kv_dtype == F8E4M3    */
+  const float* v_scales;
+  const int32_t* block_tables;     /* device [B][max_blocks]                                          */
+  const int32_t* run_request;      /* device [n_runs] request index of each run, in [0, B)            */
+  const int32_t* run_first_slot;   /* device [n_runs] logical slot of the run's first token           */
+  const int32_t* cu_run_tokens;    /* device [n_runs+1] prefix sums of tokens per run; [0] = 0 and
+                                      [n_runs] = n_tokens                                             */
+  int32_t B, n_runs, n_tokens, Hkv, D, P, max_blocks, num_pages;
+  int32_t src_dtype, kv_dtype;     /* (F32,F32) | (BF16,BF16) | (BF16,F8E4M3)                         */
+  void* timing_start;              /* optional hipEvent_t pair around the kernel, as for attention    */
+  void* timing_stop;
+} mepic_commit_params;
+
+int mepic_kv_commit(const mepic_commit_params* params, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

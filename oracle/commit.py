@@ -71,8 +71,9 @@ def kv_commit(k_pages: np.ndarray, v_pages: np.ndarray, k_scales, v_scales, k_ne
             k_idx = (((p * Hkv + h) * (D // X) + d // X) * P + s) * X + d % X      # [Hkv][D]
             v_idx = ((p * Hkv + h) * D + d) * P + s
             if kv_dtype == "f8e4m3":
-                k_pages[k_idx] = encode_e4m3(bf16_bits_to_f32(k_new[t]) / np.float32(k_scales[p]))
-                v_pages[v_idx] = encode_e4m3(bf16_bits_to_f32(v_new[t]) / np.float32(v_scales[p]))
+                with np.errstate(over="ignore"):             # a quotient beyond fp32 becomes inf and saturates
+                    k_pages[k_idx] = encode_e4m3(bf16_bits_to_f32(k_new[t]) / np.float32(k_scales[p]))
+                    v_pages[v_idx] = encode_e4m3(bf16_bits_to_f32(v_new[t]) / np.float32(v_scales[p]))
             else:                                                                   # same dtype: a copy
                 k_pages[k_idx] = k_new[t]
                 v_pages[v_idx] = v_new[t]

@@ -23,7 +23,7 @@ FLAG_ROPE_INTERLEAVED, FLAG_FORCE_GENERAL = 1, 2
 
 EXPORTS = ["mepic_strerror", "mepic_version", "mepic_pool_create", "mepic_pool_destroy", "mepic_align_request",
            "mepic_release_request", "mepic_pool_get_stats", "mepic_pool_lookup_chunk", "mepic_attn_workspace_size",
-           "mepic_attn_decode", "mepic_attn_prefill", "mepic_last_kernel"]
+           "mepic_attn_decode", "mepic_attn_prefill", "mepic_last_kernel", "mepic_kv_commit"]
 
 
 class MepicError(RuntimeError):
@@ -65,6 +65,14 @@ class AttnParams(ctypes.Structure):
                    ("timing_start", ctypes.c_void_p), ("timing_stop", ctypes.c_void_p)])
 
 
+class CommitParams(ctypes.Structure):
+    _fields_ = ([(n, ctypes.c_void_p) for n in ("k_new", "v_new", "k_pages", "v_pages", "k_scales", "v_scales",
+                                                "block_tables", "run_request", "run_first_slot", "cu_run_tokens")]
+                + [(n, ctypes.c_int32) for n in ("B", "n_runs", "n_tokens", "Hkv", "D", "P", "max_blocks", "num_pages",
+                                                 "src_dtype", "kv_dtype")]
+                + [("timing_start", ctypes.c_void_p), ("timing_stop", ctypes.c_void_p)])
+
+
 _lib = None
 
 
@@ -94,6 +102,7 @@ def load() -> ctypes.CDLL:
                                               ctypes.POINTER(ctypes.c_size_t)]
     lib.mepic_attn_decode.argtypes = [ctypes.POINTER(AttnParams), ctypes.c_void_p]
     lib.mepic_attn_prefill.argtypes = [ctypes.POINTER(AttnParams), ctypes.c_void_p]
+    lib.mepic_kv_commit.argtypes = [ctypes.POINTER(CommitParams), ctypes.c_void_p]
     _lib = lib
     return lib
 
@@ -243,6 +252,29 @@ def attn_prefill(params: AttnParams, stream=None) -> None:
     rc = load().mepic_attn_prefill(ctypes.byref(params), _stream_handle(stream))
     if rc != OK:
         raise MepicError(rc, "mepic_attn_prefill")
+
+
+def make_commit_params(k_new, v_new, k_pages, v_pages, block_tables, run_request, run_first_slot, cu_run_tokens,
+                       *, k_scales=None, v_scales=None) -> CommitParams:
+    """Fill a mepic_commit_params from torch tensors laid out as include/mepic.h states."""
+    n_tokens, Hkv, D = k_new.shape
+    B, max_blocks = block_tables.shape
+    p = CommitParams()
+    p.k_new, p.v_new, p.k_pages, p.v_pages = _p(k_new), _p(v_new), _p(k_pages), _p(v_pages)
+    p.k_scales, p.v_scales = _p(k_scales), _p(v_scales)
+    p.block_tables, p.run_request, p.run_first_slot, p.cu_run_tokens = (_p(block_tables), _p(run_request),
+                                                                       _p(run_first_slot), _p(cu_run_tokens))
+    p.B, p.n_runs, p.n_tokens, p.Hkv, p.D, p.P = B, run_request.numel(), n_tokens, Hkv, D, v_pages.shape[3]
+    p.max_blocks, p.num_pages = max_blocks, k_pages.shape[0]
+    p.src_dtype, p.kv_dtype = _dt(k_new), _dt(k_pages)
+    return p
+
+
+def kv_commit(params: CommitParams, stream=None) -> None:
+    """mepic_kv_commit on `stream` (default: torch's current stream)."""
+    rc = load().mepic_kv_commit(ctypes.byref(params), _stream_handle(stream))
+    if rc != OK:
+        raise MepicError(rc, "mepic_kv_commit")
 
 
 # ------------------------------------------------------------------------------------------------

@@ -70,3 +70,24 @@ def test_null_pointers_are_rejected_before_any_launch(mepic):
     assert lib.mepic_attn_workspace_size(ctypes.byref(p), 0, None) == mepic.ERR_INVALID
     assert lib.mepic_pool_create(4, 16, None) == mepic.ERR_INVALID
     assert lib.mepic_pool_get_stats(None, None) == mepic.ERR_INVALID
+
+
+def test_commit_shape_errors_are_rejected_before_any_launch(mepic):
+    lib = mepic.load()
+
+    def cp(**over):
+        p = mepic.CommitParams()
+        base = dict(B=1, n_runs=1, n_tokens=4, Hkv=2, D=128, P=16, max_blocks=2, num_pages=4,
+                    src_dtype=mepic.BF16, kv_dtype=mepic.BF16)
+        base.update(over)
+        for k, v in base.items():
+            setattr(p, k, v)
+        return p
+    for bad, status in ((dict(D=96), mepic.ERR_UNSUPPORTED), (dict(P=8), mepic.ERR_UNSUPPORTED),
+                        (dict(src_dtype=mepic.F32), mepic.ERR_UNSUPPORTED),
+                        (dict(src_dtype=mepic.F8E4M3, kv_dtype=mepic.F8E4M3), mepic.ERR_UNSUPPORTED),
+                        (dict(n_tokens=-1), mepic.ERR_INVALID), (dict(Hkv=0), mepic.ERR_INVALID),
+                        (dict(), mepic.ERR_INVALID)):               # all pointers null
+        assert lib.mepic_kv_commit(ctypes.byref(cp(**bad)), None) == status, bad
+    assert lib.mepic_kv_commit(ctypes.byref(cp(n_tokens=0)), None) == mepic.OK     # nothing to do: ok without pointers
+    assert lib.mepic_kv_commit(None, None) == mepic.ERR_INVALID
