@@ -47,26 +47,38 @@ __device__ __forceinline__ uint32_t quant4(const float* x, float scale) {
   return (uint32_t)w;
 }
 
-// Load the X source elements that make one destination granule and convert them.
+// The source elements that make one destination granule: 16 bytes, or 32 when bf16 is narrowed to e4m3.
 template <typename Src, typename Dst>
-__device__ __forceinline__ Granule load_convert(const Src* src, float scale) {
-  Granule g;
+struct Raw {
+  Granule g[std::is_same_v<Src, Dst> ? 1 : 2];
+};
+
+template <typename Src, typename Dst>
+__device__ __forceinline__ Raw<Src, Dst> load_raw(const Src* src) {
+  Raw<Src, Dst> r;
+  r.g[0] = reinterpret_cast<const Granule*>(src)[0];
+  if constexpr (!std::is_same_v<Src, Dst>) r.g[1] = reinterpret_cast<const Granule*>(src)[1];
+  return r;
+}
+
+template <typename Src, typename Dst>
+__device__ __forceinline__ Granule convert(const Raw<Src, Dst>& r, float scale) {
   if constexpr (std::is_same_v<Src, Dst>) {
-    g = *reinterpret_cast<const Granule*>(src);
-  } else {  // bf16 -> e4m3: 16 elements, 32 source bytes
-    const Granule a = reinterpret_cast<const Granule*>(src)[0], b = reinterpret_cast<const Granule*>(src)[1];
+    return r.g[0];
+  } else {  // bf16 -> e4m3: 16 elements
+    Granule g;
     float x[16];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      x[2 * e] = bf16_bits_to_f32(a.w[e] & 0xffffu);
-      x[2 * e + 1] = __uint_as_float(a.w[e] & 0xffff0000u);
-      x[8 + 2 * e] = bf16_bits_to_f32(b.w[e] & 0xffffu);
-      x[8 + 2 * e + 1] = __uint_as_float(b.w[e] & 0xffff0000u);
+      x[2 * e] = bf16_bits_to_f32(r.g[0].w[e] & 0xffffu);
+      x[2 * e + 1] = __uint_as_float(r.g[0].w[e] & 0xffff0000u);
+      x[8 + 2 * e] = bf16_bits_to_f32(r.g[1].w[e] & 0xffffu);
+      x[8 + 2 * e + 1] = __uint_as_float(r.g[1].w[e] & 0xffff0000u);
     }
 #pragma unroll
     for (int e = 0; e < 4; ++e) g.w[e] = quant4(x + 4 * e, scale);
+    return g;
   }
-  return g;
 }
 
 template <typename Src, typename Dst, int D, int P>
@@ -88,6 +100,22 @@ __global__ __launch_bounds__(kThreads) void kv_commit_kernel(const CommitArgs a)
   const Src* v_new = static_cast<const Src*>(a.v_new);
   Dst* k_pages = static_cast<Dst*>(a.k_pages);
   Dst* v_pages = static_cast<Dst*>(a.v_pages);
+
+  // The source addresses do not depend on the destination: issue every load of this thread first, so that
+  // the dependent chain that resolves the destinations (prefix sums -> run -> block table -> scales) runs
+  // under their latency.
+  constexpr int kUnits = (kTile * DX + kThreads - 1) / kThreads;
+  Raw<Src, Dst> rk[kUnits], rv[kUnits];
+#pragma unroll
+  for (int j = 0; j < kUnits; ++j) {
+    const int u = tid + j * kThreads;
+    const int i = u / DX, dc = u % DX;
+    if (u < kTile * DX && t0 + i < a.n_tokens) {
+      const long src_off = ((long)(t0 + i) * a.Hkv + h) * D + dc * X;
+      rk[j] = load_raw<Src, Dst>(k_new + src_off);
+      rv[j] = load_raw<Src, Dst>(v_new + src_off);
+    }
+  }
 
   if (tid < kTile) {
     const int t = t0 + tid;
@@ -122,15 +150,16 @@ __global__ __launch_bounds__(kThreads) void kv_commit_kernel(const CommitArgs a)
   }
 
   // K: granule (token i, dims X*dc ..) -> page granule (dc, slot); V: same granule converted into the LDS tile
-  for (int u = tid; u < kTile * DX; u += kThreads) {
+#pragma unroll
+  for (int j = 0; j < kUnits; ++j) {
+    const int u = tid + j * kThreads;
     const int i = u / DX, dc = u % DX;
-    const int p = s_page[i];
+    if (u >= kTile * DX) continue;
+    const int p = s_page[i];                      // >= 0 implies t0 + i < n_tokens, i.e. rk[j] / rv[j] were loaded
     if (p < 0) continue;
-    const long src_off = ((long)(t0 + i) * a.Hkv + h) * D + dc * X;
-    const Granule gk = load_convert<Src, Dst>(k_new + src_off, s_ksc[i]);
-    *reinterpret_cast<Granule*>(k_pages + ((((long)p * a.Hkv + h) * DX + dc) * P + s_slot[i]) * X) = gk;
-    const Granule gv = load_convert<Src, Dst>(v_new + src_off, s_vsc[i]);
-    *reinterpret_cast<Granule*>(s_v + i * kPitch + dc * 16) = gv;
+    *reinterpret_cast<Granule*>(k_pages + ((((long)p * a.Hkv + h) * DX + dc) * P + s_slot[i]) * X) =
+        convert<Src, Dst>(rk[j], s_ksc[i]);
+    *reinterpret_cast<Granule*>(s_v + i * kPitch + dc * 16) = convert<Src, Dst>(rv[j], s_vsc[i]);
   }
   __syncthreads();
 
