@@ -15,6 +15,8 @@
 //   PV      O^T[128 x 32 rows] += V^T (LDS) x P^T (the S^T registers, re-packed in place).
 // LDS tiles are double-buffered: one barrier per tile, the next tile's global loads are in flight during
 // the products.
+#include <type_traits>
+
 #include "attn_common.h"
 
 namespace mepic {
@@ -147,7 +149,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_bf16_kernel(const At
   auto tile_page = [&](int t, int k) { return sload(a.block_tables, bt_row + min(4 * t + k, max(n_blocks - 1, 0))); };
 
   Frag gk[2], gv[2];
-  auto load_tile = [&](int p0, int p1, int p2, int p3) {
+  auto load_tile = [&](int p0, int p1, int p2, int p3) __attribute__((always_inline)) {
     const int pg_k = (s_st < 32) ? (s_st < 16 ? p0 : p1) : (s_st < 48 ? p2 : p3);
     const size_t kb = ((size_t)pg_k * Hkv + hk) * (kD / 8 * kP) + (size_t)pc * kP + (s_st & 15);
     gk[0].u = kpages[kb];
@@ -158,7 +160,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_bf16_kernel(const At
     gv[1].u = vpages[((size_t)pg_v1 * Hkv + hk) * (kD * 2) + (tid & 255)];
   };
   // rotate the staged K granules at position (tile start + s_st), write K and V into LDS buffer `buf`
-  auto stage_tile = [&](int buf, int n0) {
+  auto stage_tile = [&](int buf, int n0) __attribute__((always_inline)) {
     Frag klo, khi;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
@@ -183,7 +185,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_bf16_kernel(const At
     for (int r = 0; r < 2; ++r) {
       const int pgi = (tid >> 8) + 2 * r, d = (tid & 255) >> 1, sh = tid & 1;
       Frag x = gv[r];
-      if (n0 + pgi * kP + 8 * sh + 8 > L) {  // slots at or past kv_len may hold anything: zero them
+      if (n0 + kTile > L && n0 + pgi * kP + 8 * sh + 8 > L) {  // slots at or past kv_len may hold anything: zero them
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
           const int n = n0 + pgi * kP + 8 * sh + 2 * w;
@@ -210,8 +212,9 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_bf16_kernel(const At
   }
   int np0 = tile_page(1, 0), np1 = tile_page(1, 1), np2 = tile_page(1, 2), np3 = tile_page(1, 3);
 
-  for (int t = 0; t < n_tiles; ++t) {
-    const int buf = t & 1, n0 = t * kTile;
+  auto tile_step = [&](int t, auto buf_tag) __attribute__((always_inline)) {
+    constexpr int buf = decltype(buf_tag)::value;  // compile-time, so that LDS addresses fold into offsets
+    const int n0 = t * kTile;
     stage_tile(buf, n0);
     __syncthreads();
     if (t + 1 < n_tiles) load_tile(np0, np1, np2, np3);
@@ -279,6 +282,10 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_bf16_kernel(const At
         }
       }
     }
+  };
+  for (int t = 0; t < n_tiles; t += 2) {
+    tile_step(t, std::integral_constant<int, 0>{});
+    if (t + 1 < n_tiles) tile_step(t + 1, std::integral_constant<int, 1>{});
   }
 
   // ---- normalise and store: lane (row l32, half) holds dims 32db + 8blk + 4half + e of its row ----
