@@ -30,11 +30,16 @@
 // head — exactly the A operand of the PV product, so probabilities never leave their lane, and the
 // matching V operand is one contiguous 16-byte piece of a V page row.
 //
-// fp8 variant: a lane owns dims 16kg..16kg+15 and 64+16kg.. (two 16-byte K granules per row); K is widened
-// with v_cvt_pk_f32_fp8, rotated, rounded to bf16 for the same QK products, and the page's K scale multiplies
-// the scores. V is never widened: PV runs on v_mfma_f32_16x16x32_fp8_fp8 with the V bytes as loaded (8 bytes
-// per lane and column tile) and the probabilities split into two e4m3 terms (p*4 = hi + lo, 8 significant
-// bits together); each step's product goes to a scratch accumulator and enters O scaled by the page's V scale.
+// fp8 variant: a lane owns dims 16kg..16kg+15 and 64+16kg.. (two 16-byte K granules per row). K codes are
+// widened to packed fp16 (v_cvt_scalef32_pk_f16_fp8, exact), rotated with packed fp16 arithmetic (two element
+// pairs per instruction; the rotation constants are stored as fp16 pairs) and go into fp16 QK products
+// (v_mfma_f32_16x16x32_f16) against Q' rounded to fp16; the page's K scale multiplies the scores. There are
+// four slot-rotation tables, R(s), R(s+32), R(s+64), R(s+96): step j uses table j mod 4 and Q' advances by
+// R(-128) once every four steps, because in this variant the advance sits on the critical path of an otherwise
+// memory-bound loop. V is never widened: PV runs on v_mfma_f32_16x16x32_fp8_fp8 with the V bytes as loaded
+// (8 bytes per lane and column tile) and the probabilities split into two e4m3 terms (p*4 = hi + lo, 8
+// significant bits together); each step's product goes to a scratch accumulator and enters O scaled by the
+// page's V scale.
 #include <type_traits>
 
 #include "attn_common.h"
@@ -66,11 +71,21 @@ constexpr int wg_per_cu(bool fp8) { return fp8 ? MEPIC_DECODE_WG_PER_CU_FP8 : ME
 constexpr int kNBuf = MEPIC_DECODE_NBUF;          // register buffers of K and V per wave (prefetch depth + 1)
 constexpr float kRescaleSlack = 6.f;  // the running maximum may lag the true one by this much (log2 units)
 
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
 union Frag {  // one 16-byte operand fragment
   uint4 u;
   bf16x8 v;
+  f16x8 hv;
   uint32_t w[4];
 };
+
+// Two fp32 -> packed fp16 pair, round to nearest even.
+__device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi) {
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+}
 
 // Two fp32 -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32 on gfx950).
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
@@ -117,8 +132,12 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
   constexpr int kNK = kFp8 ? 2 : 4;           // 16-byte K fragments per lane and product
   typedef typename std::conditional<kFp8, uint2, uint4>::type VRaw;  // V fragment per lane and column tile
   // Rotation constants, identical for every wave: one float4 {c0, s0, c1, s1} per lane and element pair.
-  __shared__ float4 rotK[16][64];  // slot rotation R(slot32): index (u*2 + h)*4 + w
-  __shared__ float4 rotS[8][64];   // step rotation R(-32):    index h*4 + w
+  // fp8: kNV tables R(slot32 + 32 v), v < kNV, entries {packed fp16 cos pair, sin pair}; Q' then advances by
+  // R(-32 kNV) once every kNV steps only (its arithmetic is on the critical path of an otherwise memory-bound loop)
+  constexpr int kNV = kFp8 ? 4 : 1;
+  typedef typename std::conditional<kFp8, float2, float4>::type RotK;
+  __shared__ RotK rotK[kNV * 16][64];  // slot rotation: index v*16 + (u*2 + h)*4 + w
+  __shared__ float4 rotS[8][64];       // step rotation R(-32 kNV): index h*4 + w
   extern __shared__ int cum[];     // cum[b] = steps of the requests before b; B + 1 entries
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n16 = lane & 15, kg = lane >> 4;
@@ -146,15 +165,22 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
   // bf16 (dims i and i + 64 sit in k-steps h and h + 2), i(p) = 16kg + p for fp8. ----
   auto freq_of = [&](int pidx) { return kFp8 ? 16 * kg + pidx : 32 * (pidx >> 3) + 8 * kg + (pidx & 7); };
   const int slot_u0 = 8 * (n16 >> 2) + (n16 & 3);
-  for (int idx = wave; idx < 24; idx += kWaves) {
-    const int h = (idx >> 2) & 1, w = idx & 3;  // idx = (u*2 + h)*4 + w for rotK, 16 + h*4 + w for rotS
-    const float pos = idx < 16 ? (float)(slot_u0 + 4 * (idx >> 3)) : -32.0f;
+  for (int idx = wave; idx < kNV * 16 + 8; idx += kWaves) {
+    const bool is_k = idx < kNV * 16;
+    const int h = (idx >> 2) & 1, w = idx & 3;  // idx = v*16 + (u*2 + h)*4 + w for rotK, kNV*16 + h*4 + w for rotS
+    const float pos = is_k ? (float)(slot_u0 + 4 * ((idx >> 3) & 1) + 32 * (idx >> 4)) : -32.0f * kNV;
     const int i = freq_of(8 * h + 2 * w);     // pairs 8h + 2w and 8h + 2w + 1 have consecutive frequencies
     const float t0 = turns_frac(pos, a.freq_hi[i], a.freq_lo[i]);
     const float t1 = turns_frac(pos, a.freq_hi[i + 1], a.freq_lo[i + 1]);
     const float4 r = make_float4(__builtin_amdgcn_cosf(t0), __builtin_amdgcn_sinf(t0), __builtin_amdgcn_cosf(t1),
                                  __builtin_amdgcn_sinf(t1));
-    if (idx < 16) rotK[idx][lane] = r; else rotS[idx - 16][lane] = r;
+    if (!is_k) {
+      rotS[idx - kNV * 16][lane] = r;
+    } else if constexpr (kFp8) {  // fp8 keys are rotated in packed fp16: {cos pair, sin pair} as two words
+      rotK[idx][lane] = make_float2(__uint_as_float(pack_f16x2(r.x, r.z)), __uint_as_float(pack_f16x2(r.y, r.w)));
+    } else {
+      rotK[idx][lane] = r;
+    }
   }
   __syncthreads();
 
@@ -213,56 +239,74 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
 
   // One step: 32 slots starting at logical slot n0. `ragged` marks the request's last step when it reaches
   // past kv_len L. ksc / vsc: the page's K and V scales (fp8; 1 for bf16).
-  auto compute = [&](Frag (&kf)[2][kNK], VRaw (&vf)[8], int n0, int L, bool ragged, float ksc, float vsc) {
+  auto compute = [&](Frag (&kf)[2][kNK], VRaw (&vf)[8], int n0, int st, int L, bool ragged, float ksc, float vsc) {
     // Q' as the B operand of the QK products
     Frag bq[4];
 #pragma unroll
     for (int h = 0; h < 2; ++h)
 #pragma unroll
       for (int e = 0; e < 8; e += 2) {
-        bq[h].w[e / 2] = pack_bf16x2(qlo[h][e], qlo[h][e + 1]);
-        bq[h + 2].w[e / 2] = pack_bf16x2(qhi[h][e], qhi[h][e + 1]);
+        bq[h].w[e / 2] = kFp8 ? pack_f16x2(qlo[h][e], qlo[h][e + 1]) : pack_bf16x2(qlo[h][e], qlo[h][e + 1]);
+        bq[h + 2].w[e / 2] = kFp8 ? pack_f16x2(qhi[h][e], qhi[h][e + 1]) : pack_bf16x2(qhi[h][e], qhi[h][e + 1]);
       }
     // Rotate the K rows by their constant slot rotation and run the two QK products, then advance Q' by
     // R(-32). Six groups of four constants each; the constants of the next group are fetched from LDS while a
     // group is computed, and scheduling barriers keep the groups apart so that only two sets are ever live.
     floatx4 sc[2];
-    float4 rc[2][4];
+    const int tv = kNV > 1 ? (st & (kNV - 1)) * 16 : 0;  // which slot-rotation table this step uses
+    RotK rc[2][4];
 #pragma unroll
-    for (int w = 0; w < 4; ++w) rc[0][w] = rotK[w][lane];
+    for (int w = 0; w < 4; ++w) rc[0][w] = rotK[tv + w][lane];
 #pragma unroll
-    for (int grp = 0; grp < 6; ++grp) {
-      float4 (&r)[4] = rc[grp & 1];
-      if (grp + 1 < 6) {
+    for (int grp = 0; grp < 4; ++grp) {
+      RotK (&r)[4] = rc[grp & 1];
+      if (grp + 1 < 4) {
 #pragma unroll
-        for (int w = 0; w < 4; ++w)
-          rc[(grp + 1) & 1][w] = (grp + 1 < 4) ? rotK[(grp + 1) * 4 + w][lane] : rotS[(grp + 1 - 4) * 4 + w][lane];
+        for (int w = 0; w < 4; ++w) rc[(grp + 1) & 1][w] = rotK[tv + (grp + 1) * 4 + w][lane];
       }
-      if (grp < 4) {
+      {
         const int u = grp >> 1, h = grp & 1;
         if (h == 0) sc[u] = floatx4{0.f, 0.f, 0.f, 0.f};
         Frag klo, khi;
+        if constexpr (kFp8) {
+          // e4m3 codes -> packed fp16 (exact), rotated with packed fp16 arithmetic (two pairs per instruction;
+          // fp16 keeps 11 significant bits, more than the bf16 operands of the bf16 path), fp16 products
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {  // pairs 8h + 2w and 8h + 2w + 1
-          float l0, l1, h0, h1;
-          if constexpr (kFp8) {
-            const f32x2 lo = (w & 1) ? __builtin_amdgcn_cvt_pk_f32_fp8((int)kf[u][0].w[2 * h + (w >> 1)], true)
-                                     : __builtin_amdgcn_cvt_pk_f32_fp8((int)kf[u][0].w[2 * h + (w >> 1)], false);
-            const f32x2 hi = (w & 1) ? __builtin_amdgcn_cvt_pk_f32_fp8((int)kf[u][1].w[2 * h + (w >> 1)], true)
-                                     : __builtin_amdgcn_cvt_pk_f32_fp8((int)kf[u][1].w[2 * h + (w >> 1)], false);
-            l0 = lo[0]; l1 = lo[1]; h0 = hi[0]; h1 = hi[1];
-          } else {
-            const uint32_t lo2 = kf[u][h].w[w], hi2 = kf[u][h + 2].w[w];
-            l0 = bf16_bits_to_f32(lo2 & 0xffffu); l1 = __uint_as_float(lo2 & 0xffff0000u);
-            h0 = bf16_bits_to_f32(hi2 & 0xffffu); h1 = __uint_as_float(hi2 & 0xffff0000u);
+          for (int w = 0; w < 4; ++w) {  // pairs 8h + 2w and 8h + 2w + 1
+            const uint32_t wl = kf[u][0].w[2 * h + (w >> 1)], wh = kf[u][1].w[2 * h + (w >> 1)];
+            const f16x2 lo = (w & 1) ? __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(wl, 1.0f, true)
+                                     : __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(wl, 1.0f, false);
+            const f16x2 hi = (w & 1) ? __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(wh, 1.0f, true)
+                                     : __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(wh, 1.0f, false);
+            const f16x2 c2 = __builtin_bit_cast(f16x2, __float_as_uint(r[w].x));
+            const f16x2 s2 = __builtin_bit_cast(f16x2, __float_as_uint(r[w].y));
+            klo.w[w] = __builtin_bit_cast(uint32_t, lo * c2 - hi * s2);
+            khi.w[w] = __builtin_bit_cast(uint32_t, hi * c2 + lo * s2);
           }
-          klo.w[w] = pack_bf16x2(l0 * r[w].x - h0 * r[w].y, l1 * r[w].z - h1 * r[w].w);  // r = {c0, s0, c1, s1}
-          khi.w[w] = pack_bf16x2(h0 * r[w].x + l0 * r[w].y, h1 * r[w].z + l1 * r[w].w);
+          sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(klo.hv, bq[h].hv, sc[u], 0, 0, 0);
+          sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(khi.hv, bq[h + 2].hv, sc[u], 0, 0, 0);
+        } else {
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {  // pairs 8h + 2w and 8h + 2w + 1
+            const uint32_t lo2 = kf[u][h].w[w], hi2 = kf[u][h + 2].w[w];
+            const float l0 = bf16_bits_to_f32(lo2 & 0xffffu), l1 = __uint_as_float(lo2 & 0xffff0000u);
+            const float h0 = bf16_bits_to_f32(hi2 & 0xffffu), h1 = __uint_as_float(hi2 & 0xffff0000u);
+            klo.w[w] = pack_bf16x2(l0 * r[w].x - h0 * r[w].y, l1 * r[w].z - h1 * r[w].w);  // r = {c0, s0, c1, s1}
+            khi.w[w] = pack_bf16x2(h0 * r[w].x + l0 * r[w].y, h1 * r[w].z + l1 * r[w].w);
+          }
+          sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(klo.v, bq[h].v, sc[u], 0, 0, 0);
+          sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(khi.v, bq[h + 2].v, sc[u], 0, 0, 0);
         }
-        sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(klo.v, bq[h].v, sc[u], 0, 0, 0);
-        sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(khi.v, bq[h + 2].v, sc[u], 0, 0, 0);
-      } else {
-        const int h = grp - 4;
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // advance Q' by R(-32 kNV) after the last step that uses it
+    if (kNV == 1 || (st & (kNV - 1)) == kNV - 1) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        float4 r[4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) r[w] = rotS[h * 4 + w][lane];
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
           const float a0 = qlo[h][2 * w], b0 = qhi[h][2 * w], a1 = qlo[h][2 * w + 1], b1 = qhi[h][2 * w + 1];
@@ -272,7 +316,6 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
           qhi[h][2 * w + 1] = b1 * r[w].z + a1 * r[w].w;
         }
       }
-      __builtin_amdgcn_sched_barrier(0);
     }
     if constexpr (kFp8) {
       sc[0] *= ksc;
@@ -477,7 +520,7 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
           constexpr int kLead = kNBuf - 1;
           const int rn = (r + kLead) % kNBuf;  // buffer of step st + kLead (free: step st - 1 used it)
           if (st + kLead < n_st) issue_step(rn, st + kLead);
-          compute(kbuf[r], vbuf[r], (j0 + kBps * st) * kP, L, ragged_end && st == n_st - 1, ks_of[r], vs_of[r]);
+          compute(kbuf[r], vbuf[r], (j0 + kBps * st) * kP, st, L, ragged_end && st == n_st - 1, ks_of[r], vs_of[r]);
         }
       }
     }
