@@ -201,6 +201,7 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
 
   floatx4 o[8];
   float m_run, l_part;
+  float v_ref = 0.f;  // fp8: O is kept in units of this reference V scale (wave-uniform), raised lazily
   float qlo[2][8], qhi[2][8];  // Q' of head n16 for the lane's 16 rotary pairs [h][e], in log2 units
 
   // K fragments of product u (row = slot slot_u0 + 4u of the step):
@@ -381,13 +382,23 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
       }
     l_part += psum;
     if constexpr (kFp8) {
-      // p * 4 = hi + lo, both e4m3 (p < 2^slack, so p * 4 < 448, the largest e4m3 value)
+      // The page's V scale rides on the probabilities: O accumulates in units of a reference scale v_ref that is
+      // at least vsc / 1.75, raised (with a rescale of O) only when a page's scale exceeds that; then
+      // p * 4 * vsc / v_ref = hi + lo, both e4m3: p < 2^slack = 64, so the product stays below 448, the largest
+      // e4m3 value. Pages with a much smaller scale lose relative precision in proportion to how little they add.
+      if (vsc > 1.75f * v_ref) {  // wave-uniform
+        const float f = v_ref / vsc;  // 0 on the first page
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt) o[nt] *= f;
+        v_ref = vsc;
+      }
+      const float ps = v_ref > 0.f ? kPScaleFp8 * vsc / v_ref : 0.f;  // a zero scale means an all-zero page
       uint32_t hi[2], lo[2];
 #pragma unroll
       for (int w = 0; w < 2; ++w) {
         float x[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) x[e] = pf[4 * w + e] * kPScaleFp8;
+        for (int e = 0; e < 4; ++e) x[e] = pf[4 * w + e] * ps;
         int hw = __builtin_amdgcn_cvt_pk_fp8_f32(x[0], x[1], 0, false);
         hw = __builtin_amdgcn_cvt_pk_fp8_f32(x[2], x[3], hw, true);
         const f32x2 b0 = __builtin_amdgcn_cvt_pk_f32_fp8(hw, false), b1 = __builtin_amdgcn_cvt_pk_f32_fp8(hw, true);
@@ -397,14 +408,11 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
         lo[w] = (uint32_t)lw;
       }
       const long a_hi = (long)(((uint64_t)hi[1] << 32) | hi[0]), a_lo = (long)(((uint64_t)lo[1] << 32) | lo[0]);
-      const float os = vsc * (1.f / kPScaleFp8);
 #pragma unroll
       for (int nt = 0; nt < 8; ++nt) {
         const long vb = (long)(((uint64_t)vf[nt].y << 32) | vf[nt].x);
-        floatx4 tmp = {0.f, 0.f, 0.f, 0.f};
-        tmp = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a_hi, vb, tmp, 0, 0, 0);
-        tmp = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a_lo, vb, tmp, 0, 0, 0);
-        o[nt] += tmp * os;
+        o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a_hi, vb, o[nt], 0, 0, 0);
+        o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a_lo, vb, o[nt], 0, 0, 0);
       }
     } else {
       Frag pa;
@@ -494,6 +502,7 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
     for (int nt = 0; nt < 8; ++nt) o[nt] = floatx4{0.f, 0.f, 0.f, 0.f};
     m_run = -INFINITY;
     l_part = 0.f;
+    v_ref = 0.f;
     {
       const float delta = (float)(sload(a.q_positions, b) - j0 * kP);
       const float qs = n16 < G ? a.qk_scale_log2 : 0.f;
@@ -540,7 +549,7 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
         if (g < G) {
           float* dst = a.part_o + (row0 + (size_t)g * a.n_splits) * kD + n16;
 #pragma unroll
-          for (int nt = 0; nt < 8; ++nt) dst[16 * nt] = o[nt][e];
+          for (int nt = 0; nt < 8; ++nt) dst[16 * nt] = kFp8 ? o[nt][e] * (v_ref * (1.f / kPScaleFp8)) : o[nt][e];
         }
       }
     }

@@ -258,3 +258,22 @@ def test_prefill_queries_in_the_middle_and_far_positions(mepic, oracle_attn):
     case.q_positions[:40] = np.arange(1000, 1040)         # request 0: sees only the first ~1000 slots
     rows = [(t, h) for t in (0, 17, 39, 40, 61, 79) for h in (0, 3, 7)]
     check(mepic, oracle_attn, case, rows=rows, expect_kernel="prefill_mfma_bf16")
+
+
+@pytest.mark.parametrize("order", ["random", "rising", "falling"])
+def test_fp8_page_scales_spread_over_four_decades(mepic, oracle_attn, order):
+    """Per-page V (and K) scales that differ by up to 10^4 between the pages of one request, in random, rising and
+    falling order along the request: the matrix-core kernel keeps its output accumulator in units of a reference
+    V scale that it raises on the way, which this exercises; the stored value of a slot is code * scale either way."""
+    st = W.decode_structure("fp8_scale_spread", 13, B=6, Hq=28, Hkv=4, D=128, P=32, theta=1e6, q_dtype="bf16",
+                            kv_dtype="f8e4m3", prefix=40, n_chunks=(2, 6), chunk_tokens=512, pool=5, question=70)
+    case = build_case(mepic, st)
+    rng = np.random.default_rng(17)
+    n = case.pages.num_pages
+    f = 10.0 ** rng.uniform(-4, 0, size=n)
+    if order != "random":                     # pages are handed out in rising order along a request
+        f = np.sort(f) if order == "rising" else np.sort(f)[::-1].copy()
+    case.pages.v_scales *= torch.from_numpy(f.astype(np.float32)) / case.pages.v_scales.max()
+    case.pages.k_scales *= torch.from_numpy((10.0 ** rng.uniform(-1, 0, size=n)).astype(np.float32))
+    check(mepic, oracle_attn, case, expect_kernel="decode_mfma_fp8")
+    check(mepic, oracle_attn, case, flags=2)
