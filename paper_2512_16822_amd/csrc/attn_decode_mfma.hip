@@ -22,8 +22,8 @@
 // Rotary embedding without per-key trigonometry: a key at position n0 + s (n0 = first slot of the
 // step) has  q^.k^ = (R(pos_q - n0) q) . (R(s) k).  R(s), s in [0, 32), is a per-lane constant (each
 // lane always handles the same two slot offsets and the same 16 frequencies) read from LDS, so a key
-// costs one constant 2x2 rotation per element pair; Q' = R(pos_q - n0) q is advanced from step to step
-// by the constant rotation R(-32).
+// costs one constant 2x2 rotation per element pair; Q' = R(pos_q - n0) q is advanced by a constant rotation
+// (with two tables of slot rotations, R(s) and R(s + 32), only every second step, by R(-64)).
 //
 // The 16 matrix rows of the QK product are the slots {0-3, 8-11, 16-19, 24-27} (+4 for the second
 // product), which makes each lane end up with the scores of 8 consecutive slots of one page for one
@@ -132,9 +132,11 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
   constexpr int kNK = kFp8 ? 2 : 4;           // 16-byte K fragments per lane and product
   typedef typename std::conditional<kFp8, uint2, uint4>::type VRaw;  // V fragment per lane and column tile
   // Rotation constants, identical for every wave: one float4 {c0, s0, c1, s1} per lane and element pair.
-  // fp8: kNV tables R(slot32 + 32 v), v < kNV, entries {packed fp16 cos pair, sin pair}; Q' then advances by
-  // R(-32 kNV) once every kNV steps only (its arithmetic is on the critical path of an otherwise memory-bound loop)
-  constexpr int kNV = kFp8 ? 4 : 1;
+  // kNV tables R(slot32 + 32 v), v < kNV (fp8 entries: {packed fp16 cos pair, sin pair}); step j uses table
+  // j mod kNV and Q' advances by R(-32 kNV) once every kNV steps only: fewer vector instructions per step, which
+  // is what limits the loop whenever the pages come from the caches (shared pages) rather than from HBM.
+  // bf16 keeps fp32 constants, so two tables are what fits beside the rest in 64 KB of static LDS.
+  constexpr int kNV = kFp8 ? 4 : 2;
   typedef typename std::conditional<kFp8, float2, float4>::type RotK;
   __shared__ RotK rotK[kNV * 16][64];  // slot rotation: index v*16 + (u*2 + h)*4 + w
   __shared__ float4 rotS[8][64];       // step rotation R(-32 kNV): index h*4 + w
