@@ -277,3 +277,40 @@ def test_fp8_page_scales_spread_over_four_decades(mepic, oracle_attn, order):
     case.pages.k_scales *= torch.from_numpy((10.0 ** rng.uniform(-1, 0, size=n)).astype(np.float32))
     check(mepic, oracle_attn, case, expect_kernel="decode_mfma_fp8")
     check(mepic, oracle_attn, case, flags=2)
+
+
+# ------------------------------------------------------------------ seeded random structures
+@pytest.mark.parametrize("seed", range(8))
+def test_random_decode_structures(mepic, oracle_attn, seed):
+    """Random batch sizes, group sizes, chunk mixes and lengths on both matrix-core decode kernels."""
+    rng = np.random.default_rng(1000 + seed)
+    fp8 = bool(seed & 1)
+    G = int(rng.choice([1, 2, 3, 4, 7, 8]))
+    Hkv = int(rng.choice([1, 2, 4]))
+    st = W.decode_structure(f"rand_decode_{seed}", 500 + seed, B=int(rng.integers(1, 40)), Hq=G * Hkv, Hkv=Hkv, D=128,
+                            P=32 if fp8 else 16, theta=float(rng.choice([1e4, 5e5, 1e6])), q_dtype="bf16",
+                            kv_dtype="f8e4m3" if fp8 else "bf16", prefix=int(rng.integers(0, 200)),
+                            n_chunks=(0, int(rng.integers(1, 9))), chunk_tokens=int(rng.integers(17, 700)),
+                            pool=int(rng.integers(1, 6)), question=int(rng.integers(0, 150)))
+    case = build_case(mepic, st)
+    n_rows = case.n_q * st.Hq
+    rows = None if n_rows <= 256 else sample_rows(case, 256, seed)
+    check(mepic, oracle_attn, case, rows=rows, expect_kernel="decode_mfma_fp8" if fp8 else "decode_mfma_bf16")
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_random_prefill_structures(mepic, oracle_attn, seed):
+    rng = np.random.default_rng(2000 + seed)
+    G = int(rng.choice([1, 2, 4, 8]))
+    Hkv = int(rng.choice([1, 2]))
+    B = int(rng.integers(1, 5))
+    st = W.prefill_structure(f"rand_prefill_{seed}", 600 + seed, B=B, Hq=G * Hkv, Hkv=Hkv, D=128, P=16, theta=5e5,
+                             n_chunks=int(rng.integers(1, 6)), chunk_tokens=int(rng.integers(30, 500)),
+                             pool=int(rng.integers(1, 4)), q_tokens=1, max_gap_pages=int(rng.integers(0, 3)))
+    st.n_q = [int(rng.integers(1, 400)) for _ in range(B)]
+    for b, n in enumerate(st.n_q):
+        st.requests[b][-1] = (0, n + int(rng.integers(0, 40)), 0)
+    case = build_case(mepic, st)
+    n_rows = case.n_q * st.Hq
+    rows = None if n_rows <= 512 else sample_rows(case, 512, seed)
+    check(mepic, oracle_attn, case, rows=rows, expect_kernel="prefill_mfma_bf16")
