@@ -260,6 +260,50 @@ typedef struct {
 
 int mepic_kv_commit(const mepic_commit_params* params, void* hip_stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * Batched decode over shared pages. The paper's related-work discussion (§6, operator-level acceleration)
+ * names shared-KV attention kernels as the complement of MEPIC: the chunk pages that many requests alias
+ * are then read (and, here, rotated) once for several requests instead of once per request. This pair of
+ * calls does that for the matrix-core decode kernels: a host planner groups the 32-slot steps of
+ * different requests that read exactly the same pages (and lie wholly below their request's kv_len) into
+ * runs served by one pass for up to 16 / (Hq/Hkv) requests; the kernel walks the runs. Results are those
+ * of mepic_attn_decode (same oracle, same tolerance); only the order of summation differs.
+ *
+ * mepic_decode_plan_build reads HOST copies of the block tables and kv_lens (the aligner wrote them to
+ * host memory in the first place) and writes the plan, a buffer of int32 words whose layout is private to
+ * the library, to host memory; the caller copies its first info.n_int32 words to the device and passes
+ * that pointer to mepic_attn_decode_batched together with the info struct. A plan is valid for exactly the
+ * block tables, kv_lens, head counts and dtype it was built from, on the device that was current when it
+ * was built. Supported: (bf16 pages, P = 16) and (fp8 pages, P = 32), D = 128, Hq/Hkv <= 16, no
+ * block_positions / block_valid_mask / interleaved pairing; otherwise MEPIC_ERR_UNSUPPORTED.
+ * Errors: MEPIC_ERR_INVALID (null pointers, kv_len beyond the table), MEPIC_ERR_CAPACITY (plan buffer or
+ * workspace too small; mepic_decode_plan_capacity gives the worst case for the plan).
+ * ---------------------------------------------------------------------------------------------- */
+typedef struct {
+  int32_t n_runs;          /* runs in the plan                                                        */
+  int32_t total_steps;     /* 32-slot steps the kernel executes per KV head                           */
+  int32_t steps_unbatched; /* steps per KV head without batching (sum over requests)                  */
+  int32_t chunk;           /* steps per wave                                                          */
+  int32_t n_splits;        /* partial results per (request, head) the workspace must hold             */
+  int32_t r_cap;           /* requests per run at most: 16 / (Hq/Hkv)                                 */
+  int32_t n_int32;         /* words of the plan buffer in use                                         */
+  int32_t B;
+} mepic_decode_plan_info;
+
+int mepic_decode_plan_capacity(int32_t B, int32_t max_blocks, int32_t P, size_t* n_int32_out);
+
+int mepic_decode_plan_build(const int32_t* block_tables_host, const int32_t* kv_lens_host, int32_t B,
+                            int32_t max_blocks, int32_t P, int32_t Hq, int32_t Hkv, int32_t kv_dtype,
+                            int32_t* plan_out_host, size_t capacity_int32, mepic_decode_plan_info* info_out);
+
+/* Workspace bytes mepic_attn_decode_batched needs for this plan. */
+int mepic_attn_decode_batched_workspace_size(const mepic_attn_params* params, const mepic_decode_plan_info* info,
+                                             size_t* bytes_out);
+
+/* Decode as mepic_attn_decode, walking the runs of `plan_device` (device copy of the planner's output). */
+int mepic_attn_decode_batched(const mepic_attn_params* params, const int32_t* plan_device,
+                              const mepic_decode_plan_info* info, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

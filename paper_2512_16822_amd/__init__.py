@@ -23,7 +23,9 @@ FLAG_ROPE_INTERLEAVED, FLAG_FORCE_GENERAL = 1, 2
 
 EXPORTS = ["mepic_strerror", "mepic_version", "mepic_pool_create", "mepic_pool_destroy", "mepic_align_request",
            "mepic_release_request", "mepic_pool_get_stats", "mepic_pool_lookup_chunk", "mepic_attn_workspace_size",
-           "mepic_attn_decode", "mepic_attn_prefill", "mepic_last_kernel", "mepic_kv_commit"]
+           "mepic_attn_decode", "mepic_attn_prefill", "mepic_last_kernel", "mepic_kv_commit",
+           "mepic_decode_plan_capacity", "mepic_decode_plan_build", "mepic_attn_decode_batched_workspace_size",
+           "mepic_attn_decode_batched"]
 
 
 class MepicError(RuntimeError):
@@ -73,6 +75,14 @@ class CommitParams(ctypes.Structure):
                 + [("timing_start", ctypes.c_void_p), ("timing_stop", ctypes.c_void_p)])
 
 
+class DecodePlanInfo(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("n_runs", "total_steps", "steps_unbatched", "chunk", "n_splits", "r_cap",
+                                              "n_int32", "B")]
+
+    def as_dict(self) -> dict:
+        return {n: int(getattr(self, n)) for n, _ in self._fields_}
+
+
 _lib = None
 
 
@@ -103,6 +113,14 @@ def load() -> ctypes.CDLL:
     lib.mepic_attn_decode.argtypes = [ctypes.POINTER(AttnParams), ctypes.c_void_p]
     lib.mepic_attn_prefill.argtypes = [ctypes.POINTER(AttnParams), ctypes.c_void_p]
     lib.mepic_kv_commit.argtypes = [ctypes.POINTER(CommitParams), ctypes.c_void_p]
+    lib.mepic_decode_plan_capacity.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                               ctypes.POINTER(ctypes.c_size_t)]
+    lib.mepic_decode_plan_build.argtypes = [ctypes.c_void_p, ctypes.c_void_p] + [ctypes.c_int32] * 6 + [
+        ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(DecodePlanInfo)]
+    lib.mepic_attn_decode_batched_workspace_size.argtypes = [ctypes.POINTER(AttnParams), ctypes.POINTER(DecodePlanInfo),
+                                                             ctypes.POINTER(ctypes.c_size_t)]
+    lib.mepic_attn_decode_batched.argtypes = [ctypes.POINTER(AttnParams), ctypes.c_void_p,
+                                              ctypes.POINTER(DecodePlanInfo), ctypes.c_void_p]
     _lib = lib
     return lib
 
@@ -252,6 +270,41 @@ def attn_prefill(params: AttnParams, stream=None) -> None:
     rc = load().mepic_attn_prefill(ctypes.byref(params), _stream_handle(stream))
     if rc != OK:
         raise MepicError(rc, "mepic_attn_prefill")
+
+
+def decode_plan_build(block_tables, kv_lens, P: int, Hq: int, Hkv: int, kv_dtype: int):
+    """mepic_decode_plan_build on host arrays (numpy int32). Returns (plan words as a numpy int32 array, info)."""
+    import numpy as np
+    bt = np.ascontiguousarray(block_tables, dtype=np.int32)
+    kl = np.ascontiguousarray(kv_lens, dtype=np.int32)
+    B, max_blocks = bt.shape
+    cap = ctypes.c_size_t()
+    rc = load().mepic_decode_plan_capacity(B, max_blocks, P, ctypes.byref(cap))
+    if rc != OK:
+        raise MepicError(rc, "mepic_decode_plan_capacity")
+    plan = np.zeros(max(int(cap.value), 1), dtype=np.int32)
+    info = DecodePlanInfo()
+    rc = load().mepic_decode_plan_build(bt.ctypes.data, kl.ctypes.data, B, max_blocks, P, Hq, Hkv, kv_dtype,
+                                        plan.ctypes.data, plan.size, ctypes.byref(info))
+    if rc != OK:
+        raise MepicError(rc, "mepic_decode_plan_build")
+    return plan[: info.n_int32].copy(), info
+
+
+def attn_decode_batched_workspace_size(params: AttnParams, info: DecodePlanInfo) -> int:
+    n = ctypes.c_size_t()
+    rc = load().mepic_attn_decode_batched_workspace_size(ctypes.byref(params), ctypes.byref(info), ctypes.byref(n))
+    if rc != OK:
+        raise MepicError(rc, "mepic_attn_decode_batched_workspace_size")
+    return int(n.value)
+
+
+def attn_decode_batched(params: AttnParams, plan_device, info: DecodePlanInfo, stream=None) -> None:
+    """mepic_attn_decode_batched on `stream` (default: torch's current stream); plan_device: int32 device tensor."""
+    rc = load().mepic_attn_decode_batched(ctypes.byref(params), _p(plan_device), ctypes.byref(info),
+                                          _stream_handle(stream))
+    if rc != OK:
+        raise MepicError(rc, "mepic_attn_decode_batched")
 
 
 def make_commit_params(k_new, v_new, k_pages, v_pages, block_tables, run_request, run_first_slot, cu_run_tokens,

@@ -158,10 +158,74 @@ int run(const mepic_attn_params* p, void* hip_stream, bool prefill) {
   return e == hipSuccess ? MEPIC_OK : MEPIC_ERR_LAUNCH;
 }
 
+// Batched decode: same checks as run(), then the plan-driven launch.
+int run_batched(const mepic_attn_params* p, const int32_t* plan, const mepic_decode_plan_info* info, void* hip_stream,
+                size_t* bytes_only) {
+  const int rc = check_shapes(p, false);
+  if (rc != MEPIC_OK) return rc;
+  if (!info) return MEPIC_ERR_INVALID;
+  const bool plain = !p->block_positions && !p->block_valid_mask &&
+                     !(p->flags & (MEPIC_FLAG_ROPE_INTERLEAVED | MEPIC_FLAG_FORCE_GENERAL));
+  const bool mfma_bf16 = p->q_dtype == MEPIC_BF16 && p->kv_dtype == MEPIC_BF16 && p->D == 128 && p->P == 16;
+  const bool mfma_fp8 = p->q_dtype == MEPIC_BF16 && p->kv_dtype == MEPIC_F8E4M3 && p->D == 128 && p->P == 32;
+  if (!plain || !(mfma_bf16 || mfma_fp8)) return MEPIC_ERR_UNSUPPORTED;
+  if (info->B != p->B || info->n_splits < 1 || info->n_runs < 0 || info->r_cap != 16 / (p->Hq / p->Hkv))
+    return MEPIC_ERR_INVALID;
+  if ((size_t)(info->n_runs + 1) * sizeof(int) > 48 * 1024) return MEPIC_ERR_UNSUPPORTED;  // run prefix sums live in LDS
+  const size_t need = (size_t)p->n_q_tokens * p->Hq * info->n_splits * (p->D + 2) * sizeof(float);
+  if (bytes_only) {
+    *bytes_only = need;
+    return MEPIC_OK;
+  }
+  if (p->n_q_tokens == 0) return MEPIC_OK;
+  if (!plan || !p->q || !p->out || !p->k_pages || !p->v_pages || !p->block_tables || !p->kv_lens || !p->q_positions)
+    return MEPIC_ERR_INVALID;
+  if (mfma_fp8 && (!p->k_scales || !p->v_scales)) return MEPIC_ERR_INVALID;
+  if (!(p->rope_theta > 0.f)) return MEPIC_ERR_INVALID;
+  if ((p->timing_start == nullptr) != (p->timing_stop == nullptr)) return MEPIC_ERR_INVALID;
+  if (!p->workspace || p->workspace_bytes < need) return MEPIC_ERR_CAPACITY;
+  if (reinterpret_cast<uintptr_t>(p->workspace) & 255u) return MEPIC_ERR_INVALID;
+
+  AttnArgs a{};
+  a.timing_start = p->timing_start; a.timing_stop = p->timing_stop;
+  a.q = p->q; a.out = p->out; a.k_pages = p->k_pages; a.v_pages = p->v_pages;
+  a.k_scales = p->k_scales; a.v_scales = p->v_scales;
+  a.block_tables = p->block_tables; a.kv_lens = p->kv_lens; a.q_positions = p->q_positions;
+  a.B = p->B; a.n_q = p->n_q_tokens; a.Hq = p->Hq; a.Hkv = p->Hkv; a.D = p->D; a.P = p->P;
+  a.max_blocks = p->max_blocks; a.num_pages = p->num_pages; a.G = p->Hq / p->Hkv;
+  a.q_dtype = p->q_dtype; a.kv_dtype = p->kv_dtype;
+  a.n_splits = info->n_splits; a.blocks_per_split = info->chunk;
+  a.plan = plan;
+  const double sm = p->sm_scale > 0.f ? (double)p->sm_scale : 1.0 / std::sqrt((double)p->D);
+  a.qk_scale_log2 = (float)(sm * 1.4426950408889634);
+  for (int i = 0; i < p->D / 2; ++i) {
+    const double f = std::pow((double)p->rope_theta, -2.0 * i / (double)p->D) / 6.283185307179586476925;
+    a.freq_hi[i] = (float)f;
+    a.freq_lo[i] = (float)(f - (double)a.freq_hi[i]);
+  }
+  float* ws = reinterpret_cast<float*>(p->workspace);
+  a.part_o = ws;
+  a.part_ml = ws + (size_t)a.n_q * a.Hq * a.n_splits * a.D;
+  g_last_kernel = mfma_fp8 ? "decode_mfma_fp8_batched" : "decode_mfma_bf16_batched";
+  const hipError_t e = launch_decode_mfma_batched(a, info->n_runs, reinterpret_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? MEPIC_OK : MEPIC_ERR_LAUNCH;
+}
+
 }  // namespace
 }  // namespace mepic
 
 extern "C" {
+
+int mepic_attn_decode_batched_workspace_size(const mepic_attn_params* params, const mepic_decode_plan_info* info,
+                                             size_t* bytes_out) {
+  if (!bytes_out) return MEPIC_ERR_INVALID;
+  return mepic::run_batched(params, nullptr, info, nullptr, bytes_out);
+}
+
+int mepic_attn_decode_batched(const mepic_attn_params* params, const int32_t* plan_device,
+                              const mepic_decode_plan_info* info, void* hip_stream) {
+  return mepic::run_batched(params, plan_device, info, hip_stream, nullptr);
+}
 
 int mepic_attn_workspace_size(const mepic_attn_params* params, int is_prefill, size_t* bytes_out) {
   if (!bytes_out) return MEPIC_ERR_INVALID;

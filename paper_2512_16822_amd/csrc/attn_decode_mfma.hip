@@ -43,6 +43,7 @@
 #include <type_traits>
 
 #include "attn_common.h"
+#include "decode_plan.h"
 
 namespace mepic {
 namespace {
@@ -125,7 +126,10 @@ __device__ __forceinline__ float sum_over_kgroups(float x) {
 
 constexpr float kPScaleFp8 = 4.f;     // probabilities (< 2^slack = 64) are multiplied by this before the e4m3 split
 
-template <bool kFp8>
+// kBatched: the sequence a KV head's waves cut into chunks is the plan's list of runs (groups of up to 16/G
+// requests stepping through identical pages together) instead of the list of requests; a lane's matrix row then
+// belongs to request row / G of the run.
+template <bool kFp8, bool kBatched>
 __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kernel(const AttnArgs a) {
   constexpr int kP = kFp8 ? 32 : 16;          // slots per page
   constexpr int kBps = kFp8 ? 1 : 2;          // blocks (pages) per step of 32 slots
@@ -145,8 +149,12 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n16 = lane & 15, kg = lane >> 4;
   const int G = a.G, Hkv = a.Hkv;
 
-  // ---- cum[] from kv_lens (a step = two blocks); one wave scans ----
-  if (wave == 0) {
+  // ---- cum[]: steps before each item of the sequence (requests, or the plan's runs) ----
+  const int n_items = kBatched ? sload(a.plan, 1) : a.B;
+  if constexpr (kBatched) {
+    for (int i = tid; i <= n_items; i += 64 * kWaves) cum[i] = a.plan[plan_off_cum(n_items) + i];
+  } else if (wave == 0) {
+    // from kv_lens (a step = two blocks); one wave scans
     int carry = 0;
     for (int base = 0; base < a.B; base += 64) {
       const int b = base + lane;
@@ -186,11 +194,12 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
   }
   __syncthreads();
 
-  const int T = uni(cum[a.B]);
+  const int T = uni(cum[n_items]);
   const int hk = (int)blockIdx.x % Hkv;
   const int wk = ((int)blockIdx.x / Hkv) * kWaves + wave, n_k = ((int)gridDim.x / Hkv) * kWaves;
-  const int chunk = max((T + n_k - 1) / n_k, a.blocks_per_split);  // blocks_per_split carries the minimum chunk
-  if (blockIdx.x == 0 && wave == 0) {  // what the merge kernel needs to find each request's partials
+  // blocks_per_split carries the minimum chunk; the planner of the batched variant fixed the chunk itself
+  const int chunk = kBatched ? sload(a.plan, 3) : max((T + n_k - 1) / n_k, a.blocks_per_split);
+  if (!kBatched && blockIdx.x == 0 && wave == 0) {  // what the merge kernel needs to find each request's partials
     for (int i = lane; i <= a.B; i += 64) a.part_meta[i] = cum[i];
     if (lane == 0) a.part_meta[a.B + 1] = chunk;
   }
@@ -432,7 +441,7 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
   // ---- walk the wave's chunk request by request ----
   int pos = pos_begin, b = 0;
   {  // request that owns the first step: largest b with cum[b] <= pos_begin
-    int lo = 0, hi = a.B - 1;
+    int lo = 0, hi = n_items - 1;
     while (lo < hi) {
       const int mid = (lo + hi + 1) >> 1;
       if (uni(cum[mid]) <= pos_begin) lo = mid; else hi = mid - 1;
@@ -447,10 +456,26 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
       c1 = uni(cum[b + 1]);
     }
     const int seg_end = min(pos_end, c1), n_st = seg_end - pos;
-    const int L = sload(a.kv_lens, b), jend = (L + kP - 1) / kP;
-    const int j0 = kBps * (pos - c0);
-    const bool ragged_end = (seg_end == c1) && (L & 31);
-    const size_t bt_row = (size_t)b * a.max_blocks;
+    // who this piece serves: the request of every matrix row, the request whose block table names the pages
+    int req0 = b, step_first = pos - c0, my_req = b, my_step = pos - c0, my_slot = 0, n_rows = G;
+    if constexpr (kBatched) {
+      const int32_t* run = a.plan + plan_off_runs(n_items) + (size_t)b * kPlanRunWords;
+      const int R = sload(run, 0);
+      n_rows = R * G;
+      req0 = sload(run, 1);
+      step_first = sload(run, 1 + kPlanMaxR) + (pos - c0);
+      const int r = n16 < n_rows ? n16 / G : 0;
+      my_req = run[1 + r];
+      my_step = run[1 + kPlanMaxR + r] + (pos - c0);
+      my_slot = run[1 + 2 * kPlanMaxR + r];
+    }
+    const int g_row = kBatched ? n16 % G : n16;        // query head (within the KV head's group) of this lane's row
+    const bool row_ok = n16 < n_rows;
+    const int L = sload(a.kv_lens, req0), jend = (L + kP - 1) / kP;
+    const int j0 = kBps * step_first;
+    // only a run of one request can reach past kv_len (the planner groups whole steps only)
+    const bool ragged_end = (step_first + n_st) * 32 > L;
+    const size_t bt_row = (size_t)req0 * a.max_blocks;
     // Page ids of the run: lane i of bt_cur holds the page of block j0 + 64*bt_win + i (clamped to the
     // request's last block), bt_nxt the 64 after those; a step reads its ids with v_readlane. Vector loads on
     // purpose: scalar loads share a counter with the LDS reads, so every wait for a rotation constant would
@@ -471,7 +496,7 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
     // qf[h] = pairs 8h.. low dims, qf[h + 2] = the same pairs' high dims (+64)
     Frag qf[4];
     {
-      const size_t qrow = ((size_t)b * a.Hq + (size_t)hk * G + (n16 < G ? n16 : 0)) * (kD / 8);
+      const size_t qrow = ((size_t)my_req * a.Hq + (size_t)hk * G + (row_ok ? g_row : 0)) * (kD / 8);
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         const int glo = kFp8 ? 2 * kg + h : 4 * h + kg;
@@ -506,8 +531,8 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
     l_part = 0.f;
     v_ref = 0.f;
     {
-      const float delta = (float)(sload(a.q_positions, b) - j0 * kP);
-      const float qs = n16 < G ? a.qk_scale_log2 : 0.f;
+      const float delta = (float)((kBatched ? a.q_positions[my_req] : sload(a.q_positions, b)) - my_step * 32);
+      const float qs = row_ok ? a.qk_scale_log2 : 0.f;
 #pragma unroll
       for (int h = 0; h < 2; ++h)
 #pragma unroll
@@ -538,18 +563,23 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
 
     // the partial of this (request, wave): un-normalised rows, reference max (log2 units), sum
     {
-      const int split = wk - c0 / chunk;
-      const size_t row0 = ((size_t)b * a.Hq + (size_t)hk * G) * a.n_splits + split;  // + g * n_splits
+      const int piece = wk - c0 / chunk;  // which of the pieces of this item the wave holds
       const float l_tot = sum_over_kgroups(l_part);
-      if (kg == 0 && n16 < G) {
-        a.part_ml[(row0 + (size_t)n16 * a.n_splits) * 2] = m_run;
-        a.part_ml[(row0 + (size_t)n16 * a.n_splits) * 2 + 1] = l_tot;
+      // partial slot of matrix row rr: [request][head][n_splits] with the request's slot base from the plan
+      auto slot_of = [&](int req, int g, int base) {
+        return ((size_t)req * a.Hq + (size_t)hk * G + g) * a.n_splits + base + piece;
+      };
+      if (kg == 0 && row_ok) {
+        const size_t sl = slot_of(my_req, g_row, my_slot);
+        a.part_ml[sl * 2] = m_run;
+        a.part_ml[sl * 2 + 1] = l_tot;
       }
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const int g = 4 * kg + e;
-        if (g < G) {
-          float* dst = a.part_o + (row0 + (size_t)g * a.n_splits) * kD + n16;
+        const int rr = 4 * kg + e;  // the accumulator element's matrix row
+        const int req = kBatched ? __shfl(my_req, rr) : b, base = kBatched ? __shfl(my_slot, rr) : 0;
+        if (rr < n_rows) {
+          float* dst = a.part_o + slot_of(req, kBatched ? rr % G : rr, base) * kD + n16;
 #pragma unroll
           for (int nt = 0; nt < 8; ++nt) dst[16 * nt] = kFp8 ? o[nt][e] * (v_ref * (1.f / kPScaleFp8)) : o[nt][e];
         }
@@ -566,6 +596,28 @@ __global__ __launch_bounds__(128) void combine_streamk_kernel(const AttnArgs a) 
   const int b = row / a.Hq;
   const int c0 = a.part_meta[b], c1 = a.part_meta[b + 1], chunk = a.part_meta[a.B + 1];
   const int ns = c1 > c0 ? (c1 - 1) / chunk - c0 / chunk + 1 : 0;
+  const float* ml = a.part_ml + (size_t)row * a.n_splits * 2;
+  const float* po = a.part_o + (size_t)row * a.n_splits * kD;
+  float m = -INFINITY;
+  for (int s = 0; s < ns; ++s) m = fmaxf(m, ml[2 * s]);
+  float num = 0.f, den = 0.f;
+  if (m != -INFINITY) {
+    for (int s = 0; s < ns; ++s) {
+      const float w = __builtin_amdgcn_exp2f(ml[2 * s] - m);
+      num += w * po[(size_t)s * kD + d];
+      den += w * ml[2 * s + 1];
+    }
+  }
+  const float o = den > 0.f ? num / den : 0.f;
+  reinterpret_cast<uint16_t*>(a.out)[(size_t)row * kD + d] = (uint16_t)f32_to_bf16_bits(o);
+}
+
+// Merge for the batched variant: request b has n_part[b] partials per head, in slots 0 .. n_part[b]-1.
+__global__ __launch_bounds__(128) void combine_batched_kernel(const AttnArgs a) {
+  const int row = blockIdx.x, d = threadIdx.x;
+  const int b = row / a.Hq;
+  const int n_runs = a.plan[1];
+  const int ns = a.plan[plan_off_npart(n_runs) + b];
   const float* ml = a.part_ml + (size_t)row * a.n_splits * 2;
   const float* po = a.part_o + (size_t)row * a.n_splits * kD;
   float m = -INFINITY;
@@ -603,15 +655,33 @@ hipError_t launch_decode_mfma(const AttnArgs& a, hipStream_t s) {
   const size_t lds = (size_t)(a.B + 1) * sizeof(int);
   if (a.timing_start) (void)hipEventRecord(reinterpret_cast<hipEvent_t>(a.timing_start), s);
   if (fp8)
-    hipLaunchKernelGGL(decode_mfma_kernel<true>, dim3(n_wg), dim3(64 * kWaves), lds, s, a);
+    hipLaunchKernelGGL((decode_mfma_kernel<true, false>), dim3(n_wg), dim3(64 * kWaves), lds, s, a);
   else
-    hipLaunchKernelGGL(decode_mfma_kernel<false>, dim3(n_wg), dim3(64 * kWaves), lds, s, a);
+    hipLaunchKernelGGL((decode_mfma_kernel<false, false>), dim3(n_wg), dim3(64 * kWaves), lds, s, a);
   hipError_t e = hipGetLastError();
   if (a.timing_stop) (void)hipEventRecord(reinterpret_cast<hipEvent_t>(a.timing_stop), s);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(combine_streamk_kernel, dim3(a.n_q * a.Hq), dim3(kD), 0, s, a);
   return hipGetLastError();
 }
+
+hipError_t launch_decode_mfma_batched(const AttnArgs& a, int n_runs, hipStream_t s) {
+  const bool fp8 = a.kv_dtype == MEPIC_F8E4M3;
+  const int n_wg = max(wg_per_cu(fp8) * compute_units() / a.Hkv, 1) * a.Hkv;
+  const size_t lds = (size_t)(n_runs + 1) * sizeof(int);
+  if (a.timing_start) (void)hipEventRecord(reinterpret_cast<hipEvent_t>(a.timing_start), s);
+  if (fp8)
+    hipLaunchKernelGGL((decode_mfma_kernel<true, true>), dim3(n_wg), dim3(64 * kWaves), lds, s, a);
+  else
+    hipLaunchKernelGGL((decode_mfma_kernel<false, true>), dim3(n_wg), dim3(64 * kWaves), lds, s, a);
+  hipError_t e = hipGetLastError();
+  if (a.timing_stop) (void)hipEventRecord(reinterpret_cast<hipEvent_t>(a.timing_stop), s);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(combine_batched_kernel, dim3(a.n_q * a.Hq), dim3(kD), 0, s, a);
+  return hipGetLastError();
+}
+
+int decode_mfma_waves_per_head(int Hkv, bool fp8) { return max(wg_per_cu(fp8) * compute_units() / Hkv, 1) * kWaves; }
 
 // Upper bound on the partials per request and the matching minimum chunk (in steps of 32 slots), from
 // host-known sizes only: with W waves per KV head and B requests a request needs about W/B pieces for an even

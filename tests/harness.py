@@ -56,6 +56,27 @@ class DeviceCase:
         self.ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
         self.params = mk(self.ws)
 
+    def prepare_batched(self):
+        """Build the batched-decode plan from the host copies of the block tables and lengths; upload it."""
+        M, st = self.M, self.case.st
+        plan, info = M.decode_plan_build(self.case.block_tables, self.case.kv_lens, st.P, st.Hq, st.Hkv,
+                                         M.F8E4M3 if st.kv_dtype == "f8e4m3" else M.BF16)
+        self.plan_info = info
+        self.plan = torch.from_numpy(plan).to(self.q.device)
+        nbytes = M.attn_decode_batched_workspace_size(self.params, info)
+        if nbytes > self.ws.numel():
+            self.ws = torch.empty(nbytes, dtype=torch.uint8, device=self.q.device)
+            self.params.workspace, self.params.workspace_bytes = self.ws.data_ptr(), nbytes
+        return info
+
+    def run_batched(self) -> np.ndarray:
+        if not hasattr(self, "plan"):
+            self.prepare_batched()
+        self.out.fill_(float("nan"))
+        self.M.attn_decode_batched(self.params, self.plan, self.plan_info)
+        torch.cuda.synchronize()
+        return self.out.to(torch.float64).cpu().numpy()
+
     def run(self) -> np.ndarray:
         (self.M.attn_prefill if self.prefill else self.M.attn_decode)(self.params)
         torch.cuda.synchronize()

@@ -1,0 +1,83 @@
+"""GPU parity of mepic_attn_decode_batched (one pass over shared pages for several requests) against the fp64
+attention oracle, and against the plain decode call."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from harness import DeviceCase, align_with_oracle, oracle_out
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+
+def check_batched(M, oracle_attn, case, rows=None):
+    dc = DeviceCase(M, case)
+    info = dc.prepare_batched()
+    got = dc.run_batched()
+    name = M.last_kernel()
+    assert name == ("decode_mfma_fp8_batched" if case.st.kv_dtype == "f8e4m3" else "decode_mfma_bf16_batched")
+    plain = dc.run()
+    want = oracle_out(oracle_attn, case, rows=rows)
+    sel = (lambda x: np.stack([x[t, h] for t, h in rows])) if rows is not None else (lambda x: x)
+    assert np.isfinite(got).all()
+    err = np.abs(sel(got) - want).max()
+    assert err <= TOL, f"max abs err {err:.3e} ({name})"
+    assert np.abs(got - plain).max() <= 2 * TOL           # the two library paths agree as well
+    return info
+
+
+@pytest.mark.parametrize("kv_dtype,P", [("bf16", 16), ("f8e4m3", 32)])
+@pytest.mark.parametrize("G", [1, 2, 4, 7, 8, 16])
+def test_shared_chunks_all_group_sizes(mepic, oracle_attn, kv_dtype, P, G):
+    st = W.decode_structure(f"batched_{kv_dtype}_{G}", 90 + G, B=11, Hq=2 * G, Hkv=2, D=128, P=P, theta=5e5, q_dtype="bf16",
+                            kv_dtype=kv_dtype, prefix=40, n_chunks=(1, 5), chunk_tokens=300, pool=3, question=45)
+    aligned, _ = align_with_oracle(st)
+    info = check_batched(mepic, oracle_attn, W.assemble(st, aligned))
+    if G <= 8:
+        assert info.total_steps < info.steps_unbatched     # something was actually batched
+
+
+def test_identical_tables_different_lengths_and_empty_requests(mepic, oracle_attn):
+    """All requests alias the same pages from slot 0 (a shared prompt), with different kv_len: whole steps are
+    batched, each request's ragged last step is not."""
+    st = W.decode_structure("same_prompt", 91, B=9, Hq=8, Hkv=2, D=128, P=16, theta=1e4, q_dtype="bf16", kv_dtype="bf16",
+                            prefix=700, n_chunks=0, chunk_tokens=16, pool=1, question=0)
+    aligned, _ = align_with_oracle(st)
+    case = W.assemble(st, aligned)
+    case.block_tables[:] = case.block_tables[0]
+    case.kv_lens[:] = np.array([701, 640, 33, 0, 1, 512, 700, 31, 96], dtype=np.int32)
+    case.q_positions[:] = np.maximum(case.kv_lens - 1, 0)
+    info = check_batched(mepic, oracle_attn, case)
+    assert info.total_steps < info.steps_unbatched
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_structures(mepic, oracle_attn, seed):
+    rng = np.random.default_rng(3000 + seed)
+    fp8 = bool(seed & 1)
+    G, Hkv = int(rng.choice([1, 2, 4, 7])), int(rng.choice([1, 2, 4]))
+    st = W.decode_structure(f"rand_batched_{seed}", 700 + seed, B=int(rng.integers(2, 50)), Hq=G * Hkv, Hkv=Hkv, D=128,
+                            P=32 if fp8 else 16, theta=5e5, q_dtype="bf16", kv_dtype="f8e4m3" if fp8 else "bf16",
+                            prefix=int(rng.integers(0, 100)), n_chunks=(0, int(rng.integers(1, 7))),
+                            chunk_tokens=int(rng.integers(33, 600)), pool=int(rng.integers(1, 4)),
+                            question=int(rng.integers(0, 120)))
+    aligned, _ = align_with_oracle(st)
+    case = W.assemble(st, aligned)
+    n_rows = case.n_q * st.Hq
+    rows = None
+    if n_rows > 256:
+        r = np.random.default_rng(seed)
+        rows = sorted({(int(r.integers(case.n_q)), int(r.integers(st.Hq))) for _ in range(256)})
+    check_batched(mepic, oracle_attn, case, rows=rows)
+
+
+@pytest.mark.parametrize("cfg,n_rows", [(2, 96), (5, 48)])
+def test_full_size_configs_sampled(mepic, oracle_attn, cfg, n_rows):
+    st = W.config(cfg)
+    aligned, _ = align_with_oracle(st)
+    case = W.assemble(st, aligned)
+    r = np.random.default_rng(cfg)
+    rows = sorted({(int(r.integers(case.n_q)), int(r.integers(st.Hq))) for _ in range(n_rows)})
+    info = check_batched(mepic, oracle_attn, case, rows=rows)
+    assert info.steps_unbatched / info.total_steps > (2.5 if cfg == 2 else 1.6)
