@@ -61,7 +61,7 @@ def visible_pairs(case) -> int:
     return total
 
 
-def time_steps(dc, steps: int, warmup: int):
+def time_steps(dc, steps: int, warmup: int, batched: bool = False):
     """Run warmup + steps calls on torch's current stream. HIP events bracket the timed region and every
     single step (torch events on the stream the library launches on); a second set of HIP events, handed to
     the library through timing_start / timing_stop, brackets the main kernel of every call alone.
@@ -69,6 +69,8 @@ def time_steps(dc, steps: int, warmup: int):
     import torch
     M = dc.M
     run = M.attn_prefill if dc.prefill else M.attn_decode
+    if batched:
+        run = lambda params: M.attn_decode_batched(params, dc.plan, dc.plan_info)
     for _ in range(warmup):
         run(dc.params)
     torch.cuda.synchronize()
@@ -200,8 +202,20 @@ def main() -> int:
         results[layout] = dict(ms=total_ms / args.steps, min_ms=min(per), kernel=M.last_kernel(),
                                kernel_ms=sum(kern) / len(kern),
                                pages=c.pages.num_pages, out=dc.out.float().cpu())
+        if layout == "shared" and not prefill and M.last_kernel().startswith("decode_mfma"):
+            # the same job with one pass over shared pages for several requests (plan built on the host)
+            t0 = time.perf_counter()
+            info = dc.prepare_batched()
+            plan_s = time.perf_counter() - t0
+            total_ms, per, kern = time_steps(dc, args.steps, args.warmup, batched=True)
+            results["shared_batched"] = dict(ms=total_ms / args.steps, min_ms=min(per), kernel=M.last_kernel(),
+                                             kernel_ms=sum(kern) / len(kern), pages=c.pages.num_pages,
+                                             out=dc.out.float().cpu(), plan=info.as_dict(), plan_build_ms=plan_s * 1e3)
         del dc
         torch.cuda.empty_cache()
+    if "shared_batched" in results:
+        diff = (results["shared_batched"]["out"] - results["shared"]["out"]).abs().max().item()
+        assert diff <= 4e-2, f"batched and plain decode disagree by {diff}"
     if len(layouts) == 2:
         assert torch.equal(results["shared"]["out"], results["duplicated"]["out"]), "layouts disagree"
 
@@ -264,8 +278,9 @@ def main() -> int:
                             n_q_tokens=case.n_q, algorithmic_bytes=abytes, useful_flops=flops),
                 roofline=roofline, cpu_baseline=cpu,
                 layouts={k: dict(ms_per_step=v["ms"], min_ms=v["min_ms"], kernel_ms=v["kernel_ms"], pages=v["pages"],
-                                 kernel=v["kernel"],
-                                 gbs=abytes / (v["ms"] * 1e-3) / 1e9) for k, v in results.items()},
+                                 kernel=v["kernel"], gbs=abytes / (v["ms"] * 1e-3) / 1e9,
+                                 **({"plan": v["plan"], "plan_build_ms": v["plan_build_ms"]} if "plan" in v else {}))
+                         for k, v in results.items()},
                 accounting=dict(pages_unique=stats["pages_in_use_unique"],
                                 pages_duplicated=stats["pages_logical_duplicated"],
                                 ratio=stats["pages_logical_duplicated"] / max(1, stats["pages_in_use_unique"]),

@@ -283,7 +283,7 @@ typedef struct {
   int32_t n_runs;          /* runs in the plan                                                        */
   int32_t total_steps;     /* 32-slot steps the kernel executes per KV head                           */
   int32_t steps_unbatched; /* steps per KV head without batching (sum over requests)                  */
-  int32_t chunk;           /* steps per wave                                                          */
+  int32_t n_waves;         /* waves per KV head the plan cuts the work for (fixed by the device)      */
   int32_t n_splits;        /* partial results per (request, head) the workspace must hold             */
   int32_t r_cap;           /* requests per run at most: 16 / (Hq/Hkv)                                 */
   int32_t n_int32;         /* words of the plan buffer in use                                         */

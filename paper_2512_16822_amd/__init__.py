@@ -76,7 +76,7 @@ class CommitParams(ctypes.Structure):
 
 
 class DecodePlanInfo(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("n_runs", "total_steps", "steps_unbatched", "chunk", "n_splits", "r_cap",
+    _fields_ = [(n, ctypes.c_int32) for n in ("n_runs", "total_steps", "steps_unbatched", "n_waves", "n_splits", "r_cap",
                                               "n_int32", "B")]
 
     def as_dict(self) -> dict:

@@ -172,6 +172,8 @@ int run_batched(const mepic_attn_params* p, const int32_t* plan, const mepic_dec
   if (info->B != p->B || info->n_splits < 1 || info->n_runs < 0 || info->r_cap != 16 / (p->Hq / p->Hkv))
     return MEPIC_ERR_INVALID;
   if ((size_t)(info->n_runs + 1) * sizeof(int) > 48 * 1024) return MEPIC_ERR_UNSUPPORTED;  // run prefix sums live in LDS
+  // the plan cut the work for the waves of the device it was built on
+  if (info->n_waves != decode_mfma_waves_per_head(p->Hkv, mfma_fp8)) return MEPIC_ERR_INVALID;
   const size_t need = (size_t)p->n_q_tokens * p->Hq * info->n_splits * (p->D + 2) * sizeof(float);
   if (bytes_only) {
     *bytes_only = need;
@@ -194,7 +196,7 @@ int run_batched(const mepic_attn_params* p, const int32_t* plan, const mepic_dec
   a.B = p->B; a.n_q = p->n_q_tokens; a.Hq = p->Hq; a.Hkv = p->Hkv; a.D = p->D; a.P = p->P;
   a.max_blocks = p->max_blocks; a.num_pages = p->num_pages; a.G = p->Hq / p->Hkv;
   a.q_dtype = p->q_dtype; a.kv_dtype = p->kv_dtype;
-  a.n_splits = info->n_splits; a.blocks_per_split = info->chunk;
+  a.n_splits = info->n_splits; a.blocks_per_split = 0;
   a.plan = plan;
   const double sm = p->sm_scale > 0.f ? (double)p->sm_scale : 1.0 / std::sqrt((double)p->D);
   a.qk_scale_log2 = (float)(sm * 1.4426950408889634);

@@ -65,7 +65,12 @@ constexpr int kWaves = 4;             // waves per workgroup
 #ifndef MEPIC_DECODE_WG_PER_CU_FP8
 #define MEPIC_DECODE_WG_PER_CU_FP8 2
 #endif
-constexpr int wg_per_cu(bool fp8) { return fp8 ? MEPIC_DECODE_WG_PER_CU_FP8 : MEPIC_DECODE_WG_PER_CU_BF16; }
+#ifndef MEPIC_DECODE_WG_PER_CU_FP8_BATCHED
+#define MEPIC_DECODE_WG_PER_CU_FP8_BATCHED 2
+#endif
+constexpr int wg_per_cu(bool fp8, bool batched = false) {
+  return fp8 ? (batched ? MEPIC_DECODE_WG_PER_CU_FP8_BATCHED : MEPIC_DECODE_WG_PER_CU_FP8) : MEPIC_DECODE_WG_PER_CU_BF16;
+}
 #ifndef MEPIC_DECODE_NBUF
 #define MEPIC_DECODE_NBUF 2
 #endif
@@ -130,7 +135,7 @@ constexpr float kPScaleFp8 = 4.f;     // probabilities (< 2^slack = 64) are mult
 // requests stepping through identical pages together) instead of the list of requests; a lane's matrix row then
 // belongs to request row / G of the run.
 template <bool kFp8, bool kBatched>
-__global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8, kBatched)) void decode_mfma_kernel(const AttnArgs a) {
   constexpr int kP = kFp8 ? 32 : 16;          // slots per page
   constexpr int kBps = kFp8 ? 1 : 2;          // blocks (pages) per step of 32 slots
   constexpr int kNK = kFp8 ? 2 : 4;           // 16-byte K fragments per lane and product
@@ -144,6 +149,8 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
   typedef typename std::conditional<kFp8, float2, float4>::type RotK;
   __shared__ RotK rotK[kNV * 16][64];  // slot rotation: index v*16 + (u*2 + h)*4 + w
   __shared__ float4 rotS[8][64];       // step rotation R(-32 kNV): index h*4 + w
+  __shared__ float2 freq_lds[kBatched ? 64 : 1];  // batched: {hi, lo} of the frequencies, index kg*16 + pair
+  __shared__ uint4 q_lds[kBatched ? kWaves * 4 : 1][64];  // batched: q of the current piece, [wave*4 + fragment][lane]
   extern __shared__ int cum[];     // cum[b] = steps of the requests before b; B + 1 entries
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n16 = lane & 15, kg = lane >> 4;
@@ -175,6 +182,13 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
   // bf16 (dims i and i + 64 sit in k-steps h and h + 2), i(p) = 16kg + p for fp8. ----
   auto freq_of = [&](int pidx) { return kFp8 ? 16 * kg + pidx : 32 * (pidx >> 3) + 8 * kg + (pidx & 7); };
   const int slot_u0 = 8 * (n16 >> 2) + (n16 & 3);
+  if constexpr (kBatched) {
+    // a piece of a run starts every few steps: its Q' set-up reads the frequencies from LDS, not from memory
+    if (wave == 0) {
+      const int i = freq_of(n16);  // lane (kg, n16) fills entry kg*16 + n16
+      freq_lds[lane] = make_float2(a.freq_hi[i], a.freq_lo[i]);
+    }
+  }
   for (int idx = wave; idx < kNV * 16 + 8; idx += kWaves) {
     const bool is_k = idx < kNV * 16;
     const int h = (idx >> 2) & 1, w = idx & 3;  // idx = v*16 + (u*2 + h)*4 + w for rotK, kNV*16 + h*4 + w for rotS
@@ -197,13 +211,18 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
   const int T = uni(cum[n_items]);
   const int hk = (int)blockIdx.x % Hkv;
   const int wk = ((int)blockIdx.x / Hkv) * kWaves + wave, n_k = ((int)gridDim.x / Hkv) * kWaves;
-  // blocks_per_split carries the minimum chunk; the planner of the batched variant fixed the chunk itself
-  const int chunk = kBatched ? sload(a.plan, 3) : max((T + n_k - 1) / n_k, a.blocks_per_split);
+  // blocks_per_split carries the minimum chunk
+  const int chunk = kBatched ? 0 : max((T + n_k - 1) / n_k, a.blocks_per_split);
   if (!kBatched && blockIdx.x == 0 && wave == 0) {  // what the merge kernel needs to find each request's partials
     for (int i = lane; i <= a.B; i += 64) a.part_meta[i] = cum[i];
     if (lane == 0) a.part_meta[a.B + 1] = chunk;
   }
-  const int pos_begin = wk * chunk, pos_end = min(pos_begin + chunk, T);
+  int pos_begin = wk * chunk, pos_end = min(pos_begin + chunk, T);
+  if constexpr (kBatched) {  // the planner placed the cuts between the waves (the host checked n_k against the plan)
+    const int32_t* cuts = a.plan + plan_off_cuts(n_items, a.B, sload(a.plan, 7));
+    pos_begin = sload(cuts, wk);
+    pos_end = sload(cuts, wk + 1);
+  }
   if (pos_begin >= pos_end) return;
 
   const uint4* kpages = reinterpret_cast<const uint4*>(a.k_pages);
@@ -218,7 +237,7 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
   // K fragments of product u (row = slot slot_u0 + 4u of the step):
   //   bf16: kf[u][j] = granule (4j + kg) of the row, j < 4 (page p0 for rows 0-7, p1 for rows 8-15);
   //   fp8:  kf[u][0] = granule kg (dims 16kg..), kf[u][1] = granule kg + 4 (dims 64 + 16kg..) of page p0.
-  auto issue_k = [&](Frag (&kf)[2][kNK], int p0, int p1) {
+  auto issue_k = [&](Frag (&kf)[2][kNK], int p0, int p1) __attribute__((always_inline)) {
     if constexpr (kFp8) {
       const size_t kb = ((size_t)p0 * Hkv + hk) * (kD / 16 * kP) + (size_t)kg * kP + slot_u0;
 #pragma unroll
@@ -236,7 +255,7 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
   };
   // V fragments, column tile nt = dim 16nt + n16: bf16: slots 8*(kg&1).. of page kg/2 (16 bytes);
   // fp8: slots 8kg.. of the page (8 bytes).
-  auto issue_v = [&](VRaw (&vf)[8], int p0, int p1) {
+  auto issue_v = [&](VRaw (&vf)[8], int p0, int p1) __attribute__((always_inline)) {
     if constexpr (kFp8) {
       const size_t vb = (((size_t)p0 * Hkv + hk) * kD + n16) * 4 + kg;
 #pragma unroll
@@ -251,7 +270,8 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
 
   // One step: 32 slots starting at logical slot n0. `ragged` marks the request's last step when it reaches
   // past kv_len L. ksc / vsc: the page's K and V scales (fp8; 1 for bf16).
-  auto compute = [&](Frag (&kf)[2][kNK], VRaw (&vf)[8], int n0, int st, int L, bool ragged, float ksc, float vsc) {
+  auto compute = [&](Frag (&kf)[2][kNK], VRaw (&vf)[8], int n0, int st, int L, bool ragged, float ksc, float vsc)
+      __attribute__((always_inline)) {
     // Q' as the B operand of the QK products
     Frag bq[4];
 #pragma unroll
@@ -438,6 +458,201 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
     }
   };
 
+  // ---- batched variant: walk the runs of the plan with the metadata of the next piece fetched during the current
+  // one, and the first K/V loads of the next piece issued during the last step of the current one (pieces are
+  // short — a handful of steps — so their start-up latency would otherwise dominate) ----
+  if constexpr (kBatched) {
+    static_assert(kNBuf == 2, "the batched walker alternates two register buffers");
+    const int32_t* runs = a.plan + plan_off_runs(n_items);
+    const int32_t* gather_list = a.plan + plan_off_gather(n_items, a.B);
+    struct Meta {
+      int b, c0, c1, pos, seg_end, n_st;              // run index, its range in the sequence, this piece of it
+      int w0, req0, step0, jlast, vreq, vstep, vslot;  // plan words (w0 .. jlast the same in every lane)
+      int bt0, bt1, L;                                 // first two windows of page ids of the leader, its kv_len
+      int gs;                                          // gather run: lane i holds step i of the piece (bt0 / bt1: its pages)
+      uint4 q0, q1, q2, q3;                            // q of this lane's row: pairs 0-7 and 8-15 low dims, then their high dims
+      int posq;                                        // position of that row's request
+    };
+    auto find = [&](Meta& m, int pos, int b) __attribute__((always_inline)) {
+      while (uni(cum[b + 1]) <= pos) ++b;
+      m.b = b; m.c0 = uni(cum[b]); m.c1 = uni(cum[b + 1]); m.pos = pos;
+      m.seg_end = min(pos_end, m.c1); m.n_st = m.seg_end - pos;
+    };
+    auto stage_a = [&](Meta& m) __attribute__((always_inline)) {  // plan words: vector loads, nothing waits here
+      const int32_t* w = runs + (size_t)m.b * kPlanRunWords;
+      const int r = n16 / G;       // rows past the run's requests read zero-filled words
+      m.w0 = w[0]; m.req0 = w[1]; m.step0 = w[1 + kPlanMaxR]; m.jlast = w[kPlanRunWords - 1];
+      m.vreq = w[1 + r]; m.vstep = w[1 + kPlanMaxR + r]; m.vslot = w[1 + 2 * kPlanMaxR + r];
+    };
+    auto stage_b = [&](Meta& m) __attribute__((always_inline)) {  // page ids of the piece's first 128 blocks and the leader's kv_len
+      const int req0 = uni(m.req0);
+      if (uni(m.w0) & kPlanGather) {  // the piece's steps and their pages from the gather section (64 at most)
+        const int32_t* g = gather_list + (size_t)(uni(m.step0) + (m.pos - m.c0) + min(lane, m.n_st - 1)) * kPlanGatherWords;
+        m.gs = g[0]; m.bt0 = g[1]; m.bt1 = g[2];
+      } else {
+        const int j0 = kBps * (uni(m.step0) + (m.pos - m.c0)), jl = uni(m.jlast);
+        const size_t row = (size_t)req0 * a.max_blocks;
+        m.bt0 = a.block_tables[row + min(j0 + lane, jl)];
+        m.bt1 = a.block_tables[row + min(j0 + 64 + lane, jl)];
+        m.gs = 0;
+      }
+      m.L = a.kv_lens[req0];
+      // q and position of the lane's row (rows past the run's requests read request 0's and are zeroed later)
+      const int n_rows = (uni(m.w0) & 0xff) * G;
+      const size_t qrow = ((size_t)m.vreq * a.Hq + (size_t)hk * G + (n16 < n_rows ? n16 % G : 0)) * (kD / 8);
+      const int g0 = kFp8 ? 2 * kg : kg, g1 = kFp8 ? 2 * kg + 1 : 4 + kg;
+      m.q0 = q4[qrow + g0]; m.q1 = q4[qrow + g1]; m.q2 = q4[qrow + 8 + g0]; m.q3 = q4[qrow + 8 + g1];
+      m.posq = a.q_positions[m.vreq];
+    };
+    Meta cur, nxt;
+    {
+      int lo = 0, hi = n_items - 1;
+      while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (uni(cum[mid]) <= pos_begin) lo = mid; else hi = mid - 1;
+      }
+      find(cur, pos_begin, lo);
+    }
+    stage_a(cur);
+    bool have_nxt = cur.seg_end < pos_end;
+    if (have_nxt) { find(nxt, cur.seg_end, cur.b); stage_a(nxt); }
+    stage_b(cur);
+    Frag kbuf[2][2][kNK];
+    VRaw vbuf[2][8];
+    float ks_of[2], vs_of[2];
+    auto issue_pages = [&](auto r_tag, int p0, int p1) __attribute__((always_inline)) {
+      constexpr int rb = decltype(r_tag)::value;
+      if constexpr (kFp8) { ks_of[rb] = a.k_scales[p0]; vs_of[rb] = a.v_scales[p0]; } else { ks_of[rb] = vs_of[rb] = 1.f; }
+      issue_k(kbuf[rb], p0, p1);
+      issue_v(vbuf[rb], p0, p1);
+    };
+    int par = 0;            // buffer of the current piece's first step
+    bool pre = false;       // that step's loads were issued during the previous piece
+    bool carry_open = false;
+    for (;;) {
+      const int word0 = uni(cur.w0), R = word0 & 0xff, n_rows = R * G, n_st = cur.n_st;
+      const bool cont = carry_open && (word0 & kPlanContinues);
+      const bool gather = (word0 & kPlanGather) != 0;  // one request, listed steps: Q' is set up anew for every step
+      const int req0 = uni(cur.req0), step_first = uni(cur.step0) + (cur.pos - cur.c0), jl = uni(cur.jlast);
+      const int my_req = cur.vreq, my_slot = cur.vslot;
+      const int my_step = gather ? __builtin_amdgcn_readlane(cur.gs, 0) : cur.vstep + (cur.pos - cur.c0);
+      const bool row_ok = n16 < n_rows;
+      const int g_row = n16 % G;
+      const int L = uni(cur.L), j0 = kBps * step_first;
+      const bool ragged_end = (step_first + n_st) * 32 > L;  // only a run of one request can reach past kv_len
+      const size_t bt_row = (size_t)req0 * a.max_blocks;
+      auto bt_load = [&](int win) { return a.block_tables[bt_row + min(j0 + 64 * win + lane, jl)]; };
+      int bt_win = 0, bt_cur = cur.bt0, bt_nxt = cur.bt1;
+      auto page = [&](int st, int k) __attribute__((always_inline)) {  // page k of step st; called with non-decreasing st
+        if (gather) return __builtin_amdgcn_readlane(k ? bt_nxt : bt_cur, st);
+        const int rel = kBps * st + k;
+        if ((rel >> 6) != bt_win) {
+          ++bt_win;
+          bt_cur = bt_nxt;
+          bt_nxt = bt_load(bt_win + 1);
+        }
+        return __builtin_amdgcn_readlane(bt_cur, rel & 63);
+      };
+      if (!pre) {
+        const int p0 = page(0, 0), p1 = kBps > 1 ? page(0, kBps - 1) : p0;
+        if (par) issue_pages(std::integral_constant<int, 1>{}, p0, p1);
+        else issue_pages(std::integral_constant<int, 0>{}, p0, p1);
+      }
+      if (have_nxt) stage_b(nxt);  // its plan words were requested a piece ago
+      if (!cont) {
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt) o[nt] = floatx4{0.f, 0.f, 0.f, 0.f};
+        m_run = -INFINITY;
+        l_part = 0.f;
+        v_ref = 0.f;
+      }
+      auto setup_q = [&](int first_slot) __attribute__((always_inline)) {  // Q' = R(pos_q - first_slot) q in log2 units
+        const float delta = (float)(cur.posq - first_slot);
+        const float qs = row_ok ? a.qk_scale_log2 : 0.f;
+        // A gather run comes here once per step. Everything below but delta is the same every time, and left to
+        // itself the compiler keeps it all (scaled q, frequencies: 64 values) in registers across the steps, which
+        // the step loop cannot afford: q waits in LDS (each lane reads back what it wrote itself), and the opaque
+        // zero in the addresses makes each call read and convert again.
+        int again = 0;
+        asm volatile("" : "+v"(again));
+        Frag qf[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) qf[i].u = q_lds[wave * 4 + i][lane + again];
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float2 f = freq_lds[kg * 16 + again + 8 * h + e];
+            const uint32_t wl = qf[h].w[e >> 1], wh = qf[h + 2].w[e >> 1];
+            const float x0 = qs * ((e & 1) ? __uint_as_float(wl & 0xffff0000u) : bf16_bits_to_f32(wl & 0xffffu));
+            const float x1 = qs * ((e & 1) ? __uint_as_float(wh & 0xffff0000u) : bf16_bits_to_f32(wh & 0xffffu));
+            const float t = turns_frac(delta, f.x, f.y);
+            const float c = __builtin_amdgcn_cosf(t), sn = __builtin_amdgcn_sinf(t);
+            qlo[h][e] = x0 * c - x1 * sn;
+            qhi[h][e] = x1 * c + x0 * sn;
+          }
+      };
+      q_lds[wave * 4 + 0][lane] = cur.q0; q_lds[wave * 4 + 1][lane] = cur.q1;
+      q_lds[wave * 4 + 2][lane] = cur.q2; q_lds[wave * 4 + 3][lane] = cur.q3;
+      setup_q(my_step * 32);
+      pre = false;
+      auto body = [&](auto r_tag, int st) __attribute__((always_inline)) {
+        constexpr int r = decltype(r_tag)::value;
+        if (st + 1 < n_st) {
+          const int p0 = page(st + 1, 0), p1 = kBps > 1 ? page(st + 1, kBps - 1) : p0;
+          issue_pages(std::integral_constant<int, r ^ 1>{}, p0, p1);
+        } else if (have_nxt) {  // the next piece's first step, while this piece's last one is computed
+          const int p0 = __builtin_amdgcn_readlane(nxt.bt0, 0);
+          const int p1 = kBps == 1 ? p0 : (uni(nxt.w0) & kPlanGather) ? __builtin_amdgcn_readlane(nxt.bt1, 0)
+                                                                     : __builtin_amdgcn_readlane(nxt.bt0, 1);
+          issue_pages(std::integral_constant<int, r ^ 1>{}, p0, p1);
+          pre = true;
+        }
+        const int n0 = gather ? 32 * __builtin_amdgcn_readlane(cur.gs, st) : (j0 + kBps * st) * kP;
+        if (gather && st > 0) setup_q(n0);
+        // a gather step always uses slot table 0 and leaves Q' alone
+        compute(kbuf[r], vbuf[r], n0, gather ? 0 : st, L, gather ? n0 + 32 > L : ragged_end && st == n_st - 1, ks_of[r],
+                vs_of[r]);
+      };
+      int st = 0;
+      if (par) { body(std::integral_constant<int, 1>{}, 0); st = 1; }
+      for (; st + 1 < n_st; st += 2) {
+        body(std::integral_constant<int, 0>{}, st);
+        body(std::integral_constant<int, 1>{}, st + 1);
+      }
+      if (st < n_st) body(std::integral_constant<int, 0>{}, st);
+      par = (par + n_st) & 1;
+
+      carry_open = have_nxt && (uni(nxt.w0) & kPlanContinues) != 0;
+      if (!carry_open) {
+        const float l_tot = sum_over_kgroups(l_part);
+        auto slot_of = [&](int req, int g, int base) {  // the plan's slot words are relative to the wave index
+          return ((size_t)req * a.Hq + (size_t)hk * G + g) * a.n_splits + base + wk;
+        };
+        if (kg == 0 && row_ok) {
+          const size_t sl = slot_of(my_req, g_row, my_slot);
+          a.part_ml[sl * 2] = m_run;
+          a.part_ml[sl * 2 + 1] = l_tot;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int rr = 4 * kg + e;  // the accumulator element's matrix row
+          const int req = __shfl(my_req, rr), base = __shfl(my_slot, rr);
+          if (rr < n_rows) {
+            float* dst = a.part_o + slot_of(req, rr % G, base) * kD + n16;
+#pragma unroll
+            for (int nt = 0; nt < 8; ++nt) dst[16 * nt] = kFp8 ? o[nt][e] * (v_ref * (1.f / kPScaleFp8)) : o[nt][e];
+          }
+        }
+      }
+      if (!have_nxt) break;
+      cur = nxt;
+      have_nxt = cur.seg_end < pos_end;
+      if (have_nxt) { find(nxt, cur.seg_end, cur.b); stage_a(nxt); }
+    }
+    return;
+  }
+
   // ---- walk the wave's chunk request by request ----
   int pos = pos_begin, b = 0;
   {  // request that owns the first step: largest b with cum[b] <= pos_begin
@@ -456,26 +671,12 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
       c1 = uni(cum[b + 1]);
     }
     const int seg_end = min(pos_end, c1), n_st = seg_end - pos;
-    // who this piece serves: the request of every matrix row, the request whose block table names the pages
-    int req0 = b, step_first = pos - c0, my_req = b, my_step = pos - c0, my_slot = 0, n_rows = G;
-    if constexpr (kBatched) {
-      const int32_t* run = a.plan + plan_off_runs(n_items) + (size_t)b * kPlanRunWords;
-      const int R = sload(run, 0);
-      n_rows = R * G;
-      req0 = sload(run, 1);
-      step_first = sload(run, 1 + kPlanMaxR) + (pos - c0);
-      const int r = n16 < n_rows ? n16 / G : 0;
-      my_req = run[1 + r];
-      my_step = run[1 + kPlanMaxR + r] + (pos - c0);
-      my_slot = run[1 + 2 * kPlanMaxR + r];
-    }
-    const int g_row = kBatched ? n16 % G : n16;        // query head (within the KV head's group) of this lane's row
-    const bool row_ok = n16 < n_rows;
-    const int L = sload(a.kv_lens, req0), jend = (L + kP - 1) / kP;
+    const int step_first = pos - c0;
+    const bool row_ok = n16 < G;  // matrix row n16 is query head n16 of the KV head's group
+    const int L = sload(a.kv_lens, b), jend = (L + kP - 1) / kP;
     const int j0 = kBps * step_first;
-    // only a run of one request can reach past kv_len (the planner groups whole steps only)
     const bool ragged_end = (step_first + n_st) * 32 > L;
-    const size_t bt_row = (size_t)req0 * a.max_blocks;
+    const size_t bt_row = (size_t)b * a.max_blocks;
     // Page ids of the run: lane i of bt_cur holds the page of block j0 + 64*bt_win + i (clamped to the
     // request's last block), bt_nxt the 64 after those; a step reads its ids with v_readlane. Vector loads on
     // purpose: scalar loads share a counter with the LDS reads, so every wait for a rotation constant would
@@ -496,7 +697,7 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
     // qf[h] = pairs 8h.. low dims, qf[h + 2] = the same pairs' high dims (+64)
     Frag qf[4];
     {
-      const size_t qrow = ((size_t)my_req * a.Hq + (size_t)hk * G + (row_ok ? g_row : 0)) * (kD / 8);
+      const size_t qrow = ((size_t)b * a.Hq + (size_t)hk * G + (row_ok ? n16 : 0)) * (kD / 8);
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         const int glo = kFp8 ? 2 * kg + h : 4 * h + kg;
@@ -531,7 +732,7 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
     l_part = 0.f;
     v_ref = 0.f;
     {
-      const float delta = (float)((kBatched ? a.q_positions[my_req] : sload(a.q_positions, b)) - my_step * 32);
+      const float delta = (float)(sload(a.q_positions, b) - step_first * 32);
       const float qs = row_ok ? a.qk_scale_log2 : 0.f;
 #pragma unroll
       for (int h = 0; h < 2; ++h)
@@ -563,23 +764,18 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
 
     // the partial of this (request, wave): un-normalised rows, reference max (log2 units), sum
     {
-      const int piece = wk - c0 / chunk;  // which of the pieces of this item the wave holds
+      const int split = wk - c0 / chunk;
+      const size_t row0 = ((size_t)b * a.Hq + (size_t)hk * G) * a.n_splits + split;  // + g * n_splits
       const float l_tot = sum_over_kgroups(l_part);
-      // partial slot of matrix row rr: [request][head][n_splits] with the request's slot base from the plan
-      auto slot_of = [&](int req, int g, int base) {
-        return ((size_t)req * a.Hq + (size_t)hk * G + g) * a.n_splits + base + piece;
-      };
-      if (kg == 0 && row_ok) {
-        const size_t sl = slot_of(my_req, g_row, my_slot);
-        a.part_ml[sl * 2] = m_run;
-        a.part_ml[sl * 2 + 1] = l_tot;
+      if (kg == 0 && n16 < G) {
+        a.part_ml[(row0 + (size_t)n16 * a.n_splits) * 2] = m_run;
+        a.part_ml[(row0 + (size_t)n16 * a.n_splits) * 2 + 1] = l_tot;
       }
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const int rr = 4 * kg + e;  // the accumulator element's matrix row
-        const int req = kBatched ? __shfl(my_req, rr) : b, base = kBatched ? __shfl(my_slot, rr) : 0;
-        if (rr < n_rows) {
-          float* dst = a.part_o + slot_of(req, kBatched ? rr % G : rr, base) * kD + n16;
+        const int g = 4 * kg + e;
+        if (g < G) {
+          float* dst = a.part_o + (row0 + (size_t)g * a.n_splits) * kD + n16;
 #pragma unroll
           for (int nt = 0; nt < 8; ++nt) dst[16 * nt] = kFp8 ? o[nt][e] * (v_ref * (1.f / kPScaleFp8)) : o[nt][e];
         }
@@ -589,49 +785,70 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8)) void decode_mfma_kern
   }
 }
 
+// Merge ns partials (reference max in log2 units, sum, un-normalised row of 128) into one bf16 output row.
+// 128 threads: four groups of 32 take every fourth partial, a thread four dims of it, so that enough loads are in
+// flight for the merge to run at memory speed when a request has tens of partials; LDS adds the groups up.
+__device__ __forceinline__ void merge_row(const float* ml, const float* po, int ns, uint16_t* out_row) {
+  __shared__ float4 num_s[4][32];
+  __shared__ float den_s[4];
+  const int part = threadIdx.x >> 5, dq = threadIdx.x & 31;
+  float m = -INFINITY;
+  for (int s = 0; s < ns; ++s) m = fmaxf(m, ml[2 * s]);
+  float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
+  float den = 0.f;
+  if (m != -INFINITY) {
+    const float4* po4 = reinterpret_cast<const float4*>(po);
+    int s = part;
+    for (; s + 4 < ns; s += 8) {  // two partials per turn
+      const float w0 = __builtin_amdgcn_exp2f(ml[2 * s] - m), w1 = __builtin_amdgcn_exp2f(ml[2 * s + 8] - m);
+      const float4 x0 = po4[(size_t)s * (kD / 4) + dq], x1 = po4[(size_t)(s + 4) * (kD / 4) + dq];
+      num.x += w0 * x0.x + w1 * x1.x; num.y += w0 * x0.y + w1 * x1.y;
+      num.z += w0 * x0.z + w1 * x1.z; num.w += w0 * x0.w + w1 * x1.w;
+      den += w0 * ml[2 * s + 1] + w1 * ml[2 * s + 9];
+    }
+    if (s < ns) {
+      const float w0 = __builtin_amdgcn_exp2f(ml[2 * s] - m);
+      const float4 x0 = po4[(size_t)s * (kD / 4) + dq];
+      num.x += w0 * x0.x; num.y += w0 * x0.y; num.z += w0 * x0.z; num.w += w0 * x0.w;
+      den += w0 * ml[2 * s + 1];
+    }
+  }
+  num_s[part][dq] = num;
+  if (dq == 0) den_s[part] = den;
+  __syncthreads();
+  if (part == 0) {
+    const float4 a1 = num_s[1][dq], a2 = num_s[2][dq], a3 = num_s[3][dq];
+    // the same order of additions in every thread
+    const float d = (den_s[0] + den_s[1]) + (den_s[2] + den_s[3]);
+    const float inv = d > 0.f ? 1.f / d : 0.f;
+    const float o0 = ((num.x + a1.x) + (a2.x + a3.x)) * inv, o1 = ((num.y + a1.y) + (a2.y + a3.y)) * inv;
+    const float o2 = ((num.z + a1.z) + (a2.z + a3.z)) * inv, o3 = ((num.w + a1.w) + (a2.w + a3.w)) * inv;
+    uint2 packed;
+    packed.x = f32_to_bf16_bits(o0) | (f32_to_bf16_bits(o1) << 16);
+    packed.y = f32_to_bf16_bits(o2) | (f32_to_bf16_bits(o3) << 16);
+    reinterpret_cast<uint2*>(out_row)[dq] = packed;
+  }
+}
+
 // Merge the partials of one (request, query head). Request b owns steps [cum[b], cum[b+1]) of its KV
 // head's sequence; the waves that cut that range wrote partials 0 .. (cum[b+1]-1)/chunk - cum[b]/chunk.
 __global__ __launch_bounds__(128) void combine_streamk_kernel(const AttnArgs a) {
-  const int row = blockIdx.x, d = threadIdx.x;
+  const int row = blockIdx.x;
   const int b = row / a.Hq;
   const int c0 = a.part_meta[b], c1 = a.part_meta[b + 1], chunk = a.part_meta[a.B + 1];
   const int ns = c1 > c0 ? (c1 - 1) / chunk - c0 / chunk + 1 : 0;
-  const float* ml = a.part_ml + (size_t)row * a.n_splits * 2;
-  const float* po = a.part_o + (size_t)row * a.n_splits * kD;
-  float m = -INFINITY;
-  for (int s = 0; s < ns; ++s) m = fmaxf(m, ml[2 * s]);
-  float num = 0.f, den = 0.f;
-  if (m != -INFINITY) {
-    for (int s = 0; s < ns; ++s) {
-      const float w = __builtin_amdgcn_exp2f(ml[2 * s] - m);
-      num += w * po[(size_t)s * kD + d];
-      den += w * ml[2 * s + 1];
-    }
-  }
-  const float o = den > 0.f ? num / den : 0.f;
-  reinterpret_cast<uint16_t*>(a.out)[(size_t)row * kD + d] = (uint16_t)f32_to_bf16_bits(o);
+  merge_row(a.part_ml + (size_t)row * a.n_splits * 2, a.part_o + (size_t)row * a.n_splits * kD, ns,
+            reinterpret_cast<uint16_t*>(a.out) + (size_t)row * kD);
 }
 
 // Merge for the batched variant: request b has n_part[b] partials per head, in slots 0 .. n_part[b]-1.
 __global__ __launch_bounds__(128) void combine_batched_kernel(const AttnArgs a) {
-  const int row = blockIdx.x, d = threadIdx.x;
+  const int row = blockIdx.x;
   const int b = row / a.Hq;
   const int n_runs = a.plan[1];
   const int ns = a.plan[plan_off_npart(n_runs) + b];
-  const float* ml = a.part_ml + (size_t)row * a.n_splits * 2;
-  const float* po = a.part_o + (size_t)row * a.n_splits * kD;
-  float m = -INFINITY;
-  for (int s = 0; s < ns; ++s) m = fmaxf(m, ml[2 * s]);
-  float num = 0.f, den = 0.f;
-  if (m != -INFINITY) {
-    for (int s = 0; s < ns; ++s) {
-      const float w = __builtin_amdgcn_exp2f(ml[2 * s] - m);
-      num += w * po[(size_t)s * kD + d];
-      den += w * ml[2 * s + 1];
-    }
-  }
-  const float o = den > 0.f ? num / den : 0.f;
-  reinterpret_cast<uint16_t*>(a.out)[(size_t)row * kD + d] = (uint16_t)f32_to_bf16_bits(o);
+  merge_row(a.part_ml + (size_t)row * a.n_splits * 2, a.part_o + (size_t)row * a.n_splits * kD, ns,
+            reinterpret_cast<uint16_t*>(a.out) + (size_t)row * kD);
 }
 
 int compute_units() {
@@ -667,8 +884,18 @@ hipError_t launch_decode_mfma(const AttnArgs& a, hipStream_t s) {
 
 hipError_t launch_decode_mfma_batched(const AttnArgs& a, int n_runs, hipStream_t s) {
   const bool fp8 = a.kv_dtype == MEPIC_F8E4M3;
-  const int n_wg = max(wg_per_cu(fp8) * compute_units() / a.Hkv, 1) * a.Hkv;
+  const int n_wg = max(wg_per_cu(fp8, true) * compute_units() / a.Hkv, 1) * a.Hkv;
   const size_t lds = (size_t)(n_runs + 1) * sizeof(int);
+  static bool lds_limit_raised = false;  // static + dynamic LDS may pass 64 KB (the caller bounds n_runs): ask for it
+  if (!lds_limit_raised) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_mfma_kernel<true, true>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 48 * 1024);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_mfma_kernel<false, true>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 48 * 1024);
+    if (e != hipSuccess) return e;
+    lds_limit_raised = true;
+  }
   if (a.timing_start) (void)hipEventRecord(reinterpret_cast<hipEvent_t>(a.timing_start), s);
   if (fp8)
     hipLaunchKernelGGL((decode_mfma_kernel<true, true>), dim3(n_wg), dim3(64 * kWaves), lds, s, a);
@@ -681,7 +908,9 @@ hipError_t launch_decode_mfma_batched(const AttnArgs& a, int n_runs, hipStream_t
   return hipGetLastError();
 }
 
-int decode_mfma_waves_per_head(int Hkv, bool fp8) { return max(wg_per_cu(fp8) * compute_units() / Hkv, 1) * kWaves; }
+int decode_mfma_waves_per_head(int Hkv, bool fp8) {  // of the batched variant: its planner cuts the sequence
+  return max(wg_per_cu(fp8, true) * compute_units() / Hkv, 1) * kWaves;
+}
 
 // Upper bound on the partials per request and the matching minimum chunk (in steps of 32 slots), from
 // host-known sizes only: with W waves per KV head and B requests a request needs about W/B pieces for an even

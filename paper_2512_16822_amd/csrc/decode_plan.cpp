@@ -10,6 +10,21 @@
 #include "attn_common.h"
 #include "decode_plan.h"
 
+// Cost of a gather step and of starting a piece of a run, in 1/16 of an ordinary step (from timings of the kernel
+// on runs of known structure).
+#ifndef MEPIC_PLAN_COST_GATHER_BF16
+#define MEPIC_PLAN_COST_GATHER_BF16 23
+#endif
+#ifndef MEPIC_PLAN_COST_START_BF16
+#define MEPIC_PLAN_COST_START_BF16 12
+#endif
+#ifndef MEPIC_PLAN_COST_GATHER_FP8
+#define MEPIC_PLAN_COST_GATHER_FP8 28
+#endif
+#ifndef MEPIC_PLAN_COST_START_FP8
+#define MEPIC_PLAN_COST_START_FP8 16
+#endif
+
 namespace mepic {
 namespace {
 
@@ -31,7 +46,8 @@ int mepic_decode_plan_capacity(int32_t B, int32_t max_blocks, int32_t P, size_t*
   if (!n_int32_out || B < 0 || max_blocks < 0 || (P != 16 && P != 32)) return MEPIC_ERR_INVALID;
   const int bps = 32 / P;
   const long steps = (long)B * ((max_blocks + bps - 1) / bps);  // every step its own run at worst
-  *n_int32_out = plan_words((int)std::min<long>(steps, 0x3fffffff / kPlanRunWords), B);
+  const int n = (int)std::min<long>(steps, 0x3fffffff / kPlanRunWords);
+  *n_int32_out = plan_words(n, B, n, kPlanMaxWaves);
   return MEPIC_OK;
 }
 
@@ -97,6 +113,7 @@ int mepic_decode_plan_build(const int32_t* block_tables, const int32_t* kv_lens,
   struct Run {
     int n;
     std::vector<StepRef> at;
+    std::vector<int> steps;  // gather run: its steps, ascending
   };
   std::vector<Run> runs;
   std::vector<char> done(total, 0);
@@ -104,7 +121,7 @@ int mepic_decode_plan_build(const int32_t* block_tables, const int32_t* kv_lens,
     for (int s = 0; s < nst[b]; ++s) {
       if (done[first[b] + s]) continue;
       const std::vector<StepRef>& g0 = groups[gid[first[b] + s]];
-      Run r{1, g0};
+      Run r{1, g0, {}};
       for (const StepRef& m : g0) done[first[m.b] + m.s] = 1;
       for (;;) {
         const StepRef lead{g0[0].b, g0[0].s + r.n};
@@ -119,39 +136,129 @@ int mepic_decode_plan_build(const int32_t* block_tables, const int32_t* kv_lens,
       runs.push_back(std::move(r));
     }
 
+  // order: per request first the runs it walks alone (a chain: consecutive in the sequence, so that one wave can
+  // keep accumulating into one partial result across them), then the shared runs it leads. The short ones among
+  // the runs it walks alone are merged into gather runs, whose steps need not be consecutive: a start-up per
+  // run costs the kernel about as much as a step.
+  int n_gather = 0;
+  {
+    std::vector<Run> ordered;
+    ordered.reserve(runs.size());
+    std::vector<std::vector<int>> alone(B), led(B);
+    for (int i = 0; i < (int)runs.size(); ++i) (runs[i].at.size() == 1 ? alone : led)[runs[i].at[0].b].push_back(i);
+    for (int b = 0; b < B; ++b) {
+      std::vector<int> loose;  // ascending: runs were formed in step order
+      for (int i : alone[b])
+        if (runs[i].n < kPlanGatherBelow)
+          for (int j = 0; j < runs[i].n; ++j) loose.push_back(runs[i].at[0].s + j);
+      for (size_t o = 0; o < loose.size(); o += kPlanGatherMax) {
+        const size_t e = std::min(loose.size(), o + (size_t)kPlanGatherMax);
+        ordered.push_back(Run{(int)(e - o), {{b, loose[o]}}, std::vector<int>(loose.begin() + o, loose.begin() + e)});
+      }
+      n_gather += (int)loose.size();
+      for (int i : alone[b])
+        if (runs[i].n >= kPlanGatherBelow) ordered.push_back(std::move(runs[i]));
+      for (int i : led[b]) ordered.push_back(std::move(runs[i]));
+    }
+    runs.swap(ordered);
+  }
   const int n_runs = (int)runs.size();
-  if (plan_words(n_runs, B) > capacity_int32) return MEPIC_ERR_CAPACITY;
+  const int W = decode_mfma_waves_per_head(Hkv, fp8);
+  if (W > kPlanMaxWaves) return MEPIC_ERR_UNSUPPORTED;
+  if (plan_words(n_runs, B, n_gather, W) > capacity_int32) return MEPIC_ERR_CAPACITY;
   int T = 0;
   for (const Run& r : runs) T += r.n;
-  const int W = decode_mfma_waves_per_head(Hkv, fp8);
-  const int chunk = std::max((T + W - 1) / W, 1);
 
-  std::memset(plan_out, 0, plan_words(n_runs, B) * sizeof(int32_t));
+  // Where the W waves of a KV head cut the sequence: by estimated time (unit: 1/16 of an ordinary step), not by
+  // step count. A gather step sets Q' up from scratch, and every piece of a run a wave starts costs a start-up.
+  // The smallest bound on a wave's time that W waves can meet, by bisection over a greedy fill.
+  std::vector<int> cuts(W + 1, T);
+  {
+    const int c_step = 16, c_gather = fp8 ? MEPIC_PLAN_COST_GATHER_FP8 : MEPIC_PLAN_COST_GATHER_BF16;
+    const int c_start = fp8 ? MEPIC_PLAN_COST_START_FP8 : MEPIC_PLAN_COST_START_BF16;
+    auto fill = [&](long bound, int* out) {  // waves needed under this bound; out: their first positions
+      int w = 0, pos = 0;
+      long acc = 0;
+      for (const Run& r : runs) {
+        const int c = r.steps.empty() ? c_step : c_gather;
+        for (int left = r.n; left > 0;) {
+          const long room = bound - acc - c_start;
+          int fit = room >= c ? (int)std::min<long>(left, room / c) : 0;
+          if (fit == 0) {
+            if (acc > 0) {  // this wave is full: the run goes to the next one
+              if (++w <= W && out) out[w] = pos;
+              acc = 0;
+              continue;
+            }
+            fit = 1;  // a bound below one step's cost cannot be met; move on all the same
+          }
+          acc += c_start + (long)fit * c;
+          pos += fit;
+          left -= fit;
+        }
+      }
+      return w + (acc > 0 ? 1 : 0);
+    };
+    long lo = c_start + c_step, hi = (long)T * std::max(c_step, c_gather) + (long)n_runs * c_start + lo;
+    while (lo < hi) {
+      const long mid = (lo + hi) / 2;
+      if (fill(mid, nullptr) <= W) hi = mid; else lo = mid + 1;
+    }
+    cuts[0] = 0;
+    fill(lo, cuts.data());  // waves past the last one needed keep the empty range [T, T)
+  }
+  auto wave_of = [&](int p) { return (int)(std::upper_bound(cuts.begin(), cuts.end(), p) - cuts.begin()) - 1; };
+
+  std::memset(plan_out, 0, plan_words(n_runs, B, n_gather, W) * sizeof(int32_t));
   int32_t* cum = plan_out + plan_off_cum(n_runs);
   int32_t* rw = plan_out + plan_off_runs(n_runs);
   int32_t* n_part = plan_out + plan_off_npart(n_runs);
-  int pos = 0, n_splits = 1;
-  for (int i = 0; i < n_runs; ++i) {
-    const Run& r = runs[i];
-    cum[i] = pos;
-    const int pieces = (pos + r.n - 1) / chunk - pos / chunk + 1;  // chunks of the head's sequence the run touches
-    int32_t* w = rw + (size_t)i * kPlanRunWords;
-    w[0] = (int32_t)r.at.size();
-    for (size_t k = 0; k < r.at.size(); ++k) {
-      w[1 + k] = r.at[k].b;
-      w[1 + kPlanMaxR + k] = r.at[k].s;
-      w[1 + 2 * kPlanMaxR + k] = n_part[r.at[k].b];
-      n_part[r.at[k].b] += pieces;
-      n_splits = std::max(n_splits, (int)n_part[r.at[k].b]);
+  int32_t* gather = plan_out + plan_off_gather(n_runs, B);
+  int pos = 0, n_splits = 1, n_listed = 0;
+  for (int i = 0; i < n_runs;) {
+    // a chain: a maximal stretch of consecutive one-request runs of the same request (or one shared run)
+    int j = i + 1, len = runs[i].n;
+    if (runs[i].at.size() == 1)
+      while (j < n_runs && runs[j].at.size() == 1 && runs[j].at[0].b == runs[i].at[0].b) len += runs[j++].n;
+    const int head_wave = wave_of(pos);
+    const int pieces = wave_of(pos + len - 1) - head_wave + 1;  // waves that touch the chain: one partial result each
+    std::vector<int> base(runs[i].at.size());
+    for (size_t k = 0; k < runs[i].at.size(); ++k) {
+      base[k] = n_part[runs[i].at[k].b];
+      n_part[runs[i].at[k].b] += pieces;
+      n_splits = std::max(n_splits, (int)n_part[runs[i].at[k].b]);
     }
-    pos += r.n;
+    for (int q = i; q < j; ++q) {
+      const Run& r = runs[q];
+      cum[q] = pos;
+      int32_t* w = rw + (size_t)q * kPlanRunWords;
+      w[0] = (int32_t)r.at.size() | (q > i ? kPlanContinues : 0) | (r.steps.empty() ? 0 : kPlanGather);
+      w[kPlanRunWords - 1] = std::max((kv_lens[r.at[0].b] + P - 1) / P - 1, 0);  // clamp for the page-id loads
+      for (size_t k = 0; k < r.at.size(); ++k) {
+        w[1 + k] = r.at[k].b;
+        w[1 + kPlanMaxR + k] = r.steps.empty() ? r.at[k].s : n_listed;
+        // the kernel adds its wave index: every run of a chain lands on the chain's slots
+        w[1 + 2 * kPlanMaxR + k] = base[k] - head_wave;
+      }
+      for (int st : r.steps) {
+        const int32_t* pages = block_tables + (size_t)r.at[0].b * max_blocks + (size_t)st * bps;
+        int32_t* g = gather + (size_t)n_listed++ * kPlanGatherWords;
+        // the second block of a request's last step may lie past its blocks: the kernel masks those slots, the
+        // page it reads them from only has to exist
+        const bool second = bps == 2 && st * bps + 1 < (kv_lens[r.at[0].b] + P - 1) / P;
+        g[0] = st; g[1] = pages[0]; g[2] = second ? pages[1] : pages[0];
+      }
+      pos += r.n;
+    }
+    i = j;
   }
   cum[n_runs] = pos;
-  plan_out[0] = kPlanMagic; plan_out[1] = n_runs; plan_out[2] = T; plan_out[3] = chunk; plan_out[4] = n_splits;
-  plan_out[5] = B; plan_out[6] = r_cap; plan_out[7] = 0;
+  std::copy(cuts.begin(), cuts.end(), plan_out + plan_off_cuts(n_runs, B, n_gather));
+  plan_out[0] = kPlanMagic; plan_out[1] = n_runs; plan_out[2] = T; plan_out[3] = W; plan_out[4] = n_splits;
+  plan_out[5] = B; plan_out[6] = r_cap; plan_out[7] = n_gather;
 
-  info_out->n_runs = n_runs; info_out->total_steps = T; info_out->chunk = chunk; info_out->n_splits = n_splits;
-  info_out->r_cap = r_cap; info_out->steps_unbatched = total; info_out->n_int32 = (int32_t)plan_words(n_runs, B);
+  info_out->n_runs = n_runs; info_out->total_steps = T; info_out->n_waves = W; info_out->n_splits = n_splits;
+  info_out->r_cap = r_cap; info_out->steps_unbatched = total; info_out->n_int32 = (int32_t)plan_words(n_runs, B, n_gather, W);
   info_out->B = B;
   return MEPIC_OK;
 }

@@ -8,22 +8,35 @@ import workloads as W
 from harness import align_with_oracle
 
 HEADER, MAXR = 8, 16
-RUN_WORDS = 1 + 3 * MAXR
+RUN_WORDS = 2 + 3 * MAXR
+
+
+GATHER_WORDS, GATHER_MAX, GATHER_BELOW = 3, 64, 4
 
 
 def parse(plan, info):
-    n, B = info.n_runs, info.B
+    n, B, n_gather = info.n_runs, info.B, int(plan[7])
     assert plan[0] == 0x4D455049 and plan[1] == n and plan[5] == B
     cum = plan[HEADER: HEADER + n + 1]
     runs = plan[HEADER + n + 1: HEADER + n + 1 + n * RUN_WORDS].reshape(n, RUN_WORDS)
-    n_part = plan[HEADER + n + 1 + n * RUN_WORDS:]
-    assert n_part.size == B
-    return cum, runs, n_part
+    off = HEADER + n + 1 + n * RUN_WORDS
+    n_part = plan[off: off + B]
+    gather = plan[off + B:]
+    cuts = plan[off + B + n_gather * GATHER_WORDS:]
+    gather = plan[off + B: off + B + n_gather * GATHER_WORDS]
+    assert cuts.size == info.n_waves + 1 == plan[3] + 1 and plan.size == info.n_int32
+    return cum, runs, n_part, gather.reshape(n_gather, GATHER_WORDS), cuts
 
 
 def check_plan(M, bt, kv_lens, P, Hq, Hkv, kv_dtype):
     plan, info = M.decode_plan_build(bt, kv_lens, P, Hq, Hkv, kv_dtype)
-    cum, runs, n_part = parse(plan, info)
+    cum, runs, n_part, gather, cuts = parse(plan, info)
+    listed = 0
+    # the waves' ranges tile the sequence of steps; wave_of(p) = the wave whose range holds position p
+    assert cuts[0] == 0 and cuts[-1] == info.total_steps and (np.diff(cuts) >= 0).all()
+    wave_of = lambda p: int(np.searchsorted(cuts, p, side="right")) - 1
+    # cut by estimated time, not by count, but no wave gets more than twice its even share of steps
+    assert int(np.diff(cuts).max(initial=0)) <= 2 * -(-info.total_steps // info.n_waves) + 2
     bps, G = 32 // P, Hq // Hkv
     B = bt.shape[0]
     nst = [(-(-int(L) // P) + bps - 1) // bps for L in kv_lens]
@@ -31,24 +44,52 @@ def check_plan(M, bt, kv_lens, P, Hq, Hkv, kv_dtype):
     seen = [np.zeros(n, dtype=np.int32) for n in nst]
     used = [0] * B
     pos = 0
+    chain_base, chain_head_wave = None, None
     for i, w in enumerate(runs):
-        R = int(w[0])
+        R, cont, is_gather = int(w[0]) & 0xFF, bool(int(w[0]) & 0x100), bool(int(w[0]) & 0x200)
         req, step0, slot = w[1:1 + R], w[1 + MAXR:1 + MAXR + R], w[1 + 2 * MAXR:1 + 2 * MAXR + R]
         n = int(cum[i + 1] - cum[i])
         assert cum[i] == pos and n >= 1 and 1 <= R <= info.r_cap and len(set(req.tolist())) == R
-        pieces = (pos + n - 1) // info.chunk - pos // info.chunk + 1
+        if cont:                                            # continues the previous one-request run of the same request
+            prev = runs[i - 1]
+            assert R == 1 and (int(prev[0]) & 0xFF) == 1 and prev[1] == req[0]
+        else:                                               # head of a chain: its slots cover every wave the chain touches
+            j, length = i + 1, n
+            while j < len(runs) and int(runs[j][0]) & 0x100:
+                length += int(cum[j + 1] - cum[j])
+                j += 1
+            pieces = wave_of(pos + length - 1) - wave_of(pos) + 1
+            chain_base = [used[int(b)] for b in req]
+            chain_head_wave = wave_of(pos)
+            for b in req:
+                used[int(b)] += pieces
+        for k in range(R):
+            assert slot[k] == chain_base[k] - chain_head_wave       # the kernel adds its wave index
+        if is_gather:                                       # one request; listed steps, ascending, with their pages
+            b, L = int(req[0]), int(kv_lens[int(req[0])])
+            assert R == 1 and n <= GATHER_MAX and step0[0] == listed
+            entries = gather[listed:listed + n]
+            listed += n
+            assert (np.diff(entries[:, 0]) > 0).all()
+            for st, p0, p1 in entries.tolist():
+                seen[b][st] += 1
+                assert p0 == bt[b, st * bps]
+                second = bps == 2 and st * bps + 1 < -(-L // P)
+                assert p1 == (bt[b, st * bps + 1] if second else p0)
+            pos += n
+            continue
+        if R == 1:                                          # short one-request runs were gathered
+            assert n >= GATHER_BELOW
         for k in range(R):
             b, s0 = int(req[k]), int(step0[k])
             seen[b][s0:s0 + n] += 1
-            assert slot[k] == used[b]                       # slots of a request are handed out in run order
-            used[b] += pieces
         for j in range(n):                                  # identical pages, and whole steps when shared
             tuples = {tuple(bt[int(req[k]), (int(step0[k]) + j) * bps:(int(step0[k]) + j + 1) * bps].tolist()) for k in range(R)}
             assert len(tuples) == 1
             if R > 1:
                 assert all((int(step0[k]) + j + 1) * 32 <= int(kv_lens[int(req[k])]) for k in range(R))
         pos += n
-    assert pos == info.total_steps == cum[-1]
+    assert pos == info.total_steps == cum[-1] and listed == len(gather)
     assert all((s == 1).all() for s in seen), "every (request, step) exactly once"
     assert used == n_part.tolist() and info.n_splits == max(1, max(used, default=1))
     return info
