@@ -204,9 +204,13 @@ def main() -> int:
                                pages=c.pages.num_pages, out=dc.out.float().cpu())
         if layout == "shared" and not prefill and M.last_kernel().startswith("decode_mfma"):
             # the same job with one pass over shared pages for several requests (plan built on the host)
-            t0 = time.perf_counter()
             info = dc.prepare_batched()
-            plan_s = time.perf_counter() - t0
+            plan_s = 1e9
+            for _ in range(3):   # the host planner alone (the upload and the workspace are not part of it)
+                t0 = time.perf_counter()
+                M.decode_plan_build(c.block_tables, c.kv_lens, st.P, st.Hq, st.Hkv,
+                                    M.F8E4M3 if st.kv_dtype == "f8e4m3" else M.BF16)
+                plan_s = min(plan_s, time.perf_counter() - t0)
             total_ms, per, kern = time_steps(dc, args.steps, args.warmup, batched=True)
             results["shared_batched"] = dict(ms=total_ms / args.steps, min_ms=min(per), kernel=M.last_kernel(),
                                              kernel_ms=sum(kern) / len(kern), pages=c.pages.num_pages,

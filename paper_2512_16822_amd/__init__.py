@@ -282,7 +282,7 @@ def decode_plan_build(block_tables, kv_lens, P: int, Hq: int, Hkv: int, kv_dtype
     rc = load().mepic_decode_plan_capacity(B, max_blocks, P, ctypes.byref(cap))
     if rc != OK:
         raise MepicError(rc, "mepic_decode_plan_capacity")
-    plan = np.zeros(max(int(cap.value), 1), dtype=np.int32)
+    plan = np.empty(max(int(cap.value), 1), dtype=np.int32)  # worst case; the library writes the words it uses
     info = DecodePlanInfo()
     rc = load().mepic_decode_plan_build(bt.ctypes.data, kl.ctypes.data, B, max_blocks, P, Hq, Hkv, kv_dtype,
                                         plan.ctypes.data, plan.size, ctypes.byref(info))

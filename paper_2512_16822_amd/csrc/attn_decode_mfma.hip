@@ -462,7 +462,6 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8, kBatched)) void decode
   // one, and the first K/V loads of the next piece issued during the last step of the current one (pieces are
   // short — a handful of steps — so their start-up latency would otherwise dominate) ----
   if constexpr (kBatched) {
-    static_assert(kNBuf == 2, "the batched walker alternates two register buffers");
     const int32_t* runs = a.plan + plan_off_runs(n_items);
     const int32_t* gather_list = a.plan + plan_off_gather(n_items, a.B);
     struct Meta {

@@ -4,7 +4,6 @@
 // are then read and rotated once instead of once per request).
 #include <algorithm>
 #include <cstring>
-#include <unordered_map>
 #include <vector>
 
 #include "attn_common.h"
@@ -75,39 +74,63 @@ int mepic_decode_plan_build(const int32_t* block_tables, const int32_t* kv_lens,
   const int total = first[B];
 
   // group id of every step: steps wholly below kv_len whose pages coincide are grouped, at most r_cap requests
-  // per group and a request at most once per group
-  std::vector<int> gid(total, -1);
-  std::vector<std::vector<StepRef>> groups;
+  // per group and a request at most once per group. Groups are stored back to back: group g = members
+  // gm[goff[g] .. goff[g + 1]), ascending in (request, step).
+  std::vector<int> gid(total, -1), goff{0};
+  std::vector<StepRef> gm;
+  gm.reserve(total);
+  goff.reserve(total + 1);
   {
-    std::unordered_map<uint64_t, std::vector<StepRef>> by_key;
-    by_key.reserve((size_t)total * 2);
-    for (int b = 0; b < B; ++b)
-      for (int s = 0; s < nst[b]; ++s)
-        if ((s + 1) * 32 <= kv_lens[b]) by_key[key_of(block_tables + (size_t)b * max_blocks + (size_t)s * bps, bps)].push_back({b, s});
+    // steps with the same pages, as singly linked lists in ascending (request, step) order; the lists' heads sit in
+    // an open-addressing table keyed by the pages
+    size_t cap = 64;
+    while (cap < 2 * (size_t)total) cap <<= 1;
+    std::vector<uint64_t> slot_key(cap);
+    std::vector<int> slot_head(cap, -1), next(total, -1);
+    std::vector<StepRef> ref(total);
+    for (int b = B - 1; b >= 0; --b)
+      for (int s = nst[b] - 1; s >= 0; --s) {
+        const int me = first[b] + s;
+        ref[me] = {b, s};
+        if ((s + 1) * 32 > kv_lens[b]) continue;
+        const uint64_t key = key_of(block_tables + (size_t)b * max_blocks + (size_t)s * bps, bps);
+        size_t h = (size_t)((key * 0x9e3779b97f4a7c15ull) >> 20) & (cap - 1);
+        while (slot_head[h] >= 0 && slot_key[h] != key) h = (h + 1) & (cap - 1);
+        slot_key[h] = key;
+        next[me] = slot_head[h];  // -1 for the first of its kind
+        slot_head[h] = me;
+      }
     for (int b = 0; b < B; ++b)  // deterministic order: by first member
       for (int s = 0; s < nst[b]; ++s) {
-        if (gid[first[b] + s] >= 0 || (s + 1) * 32 > kv_lens[b]) continue;
-        auto it = by_key.find(key_of(block_tables + (size_t)b * max_blocks + (size_t)s * bps, bps));
-        std::vector<StepRef>& members = it->second;  // ascending (b, s)
-        std::vector<StepRef> cur;
-        for (const StepRef& m : members) {
-          if (gid[first[m.b] + m.s] >= 0) continue;
-          bool dup = false;
-          for (const StepRef& c : cur) dup = dup || c.b == m.b;
-          if (dup) continue;  // a second occurrence in the same request waits for a later group
-          cur.push_back(m);
-          if ((int)cur.size() == r_cap) break;
+        const int me = first[b] + s;
+        if (gid[me] >= 0) continue;
+        const int g = (int)goff.size() - 1;
+        if ((s + 1) * 32 > kv_lens[b]) {  // a ragged last step is a group of its own
+          gid[me] = g;
+          gm.push_back({b, s});
+          goff.push_back((int)gm.size());
+          continue;
         }
-        for (const StepRef& c : cur) gid[first[c.b] + c.s] = (int)groups.size();
-        groups.push_back(std::move(cur));
+        // the ungrouped steps of the list from here on (everything before `me` is grouped already); a step that
+        // joins the group is unlinked, so that later walks pass over ungrouped steps only
+        const size_t at = gm.size();
+        int last_b = -1;  // the list is ascending in request: a request's second occurrence follows its first
+        for (int m = me, prev = -1; m >= 0 && (int)(gm.size() - at) < r_cap;) {
+          const int nx = next[m];
+          if (ref[m].b == last_b) {  // a second occurrence in one request waits for a later group
+            prev = m;
+          } else {
+            gid[m] = g;
+            gm.push_back(ref[m]);
+            last_b = ref[m].b;
+            if (prev >= 0) next[prev] = nx;
+          }
+          m = nx;
+        }
+        goff.push_back((int)gm.size());
       }
-    for (int b = 0; b < B; ++b)
-      for (int s = 0; s < nst[b]; ++s)
-        if (gid[first[b] + s] < 0) {  // ragged last steps
-          gid[first[b] + s] = (int)groups.size();
-          groups.push_back({{b, s}});
-        }
   }
+  auto group_size = [&](int g) { return goff[g + 1] - goff[g]; };
 
   // runs: follow a group while all of its members step forward together into one and the same group
   struct Run {
@@ -120,17 +143,19 @@ int mepic_decode_plan_build(const int32_t* block_tables, const int32_t* kv_lens,
   for (int b = 0; b < B; ++b)
     for (int s = 0; s < nst[b]; ++s) {
       if (done[first[b] + s]) continue;
-      const std::vector<StepRef>& g0 = groups[gid[first[b] + s]];
-      Run r{1, g0, {}};
-      for (const StepRef& m : g0) done[first[m.b] + m.s] = 1;
+      const int g0 = gid[first[b] + s], n0 = group_size(g0);
+      const StepRef* m0 = gm.data() + goff[g0];
+      Run r{1, std::vector<StepRef>(m0, m0 + n0), {}};
+      for (int k = 0; k < n0; ++k) done[first[m0[k].b] + m0[k].s] = 1;
       for (;;) {
-        const StepRef lead{g0[0].b, g0[0].s + r.n};
+        const StepRef lead{m0[0].b, m0[0].s + r.n};
         if (lead.s >= nst[lead.b] || done[first[lead.b] + lead.s]) break;
-        const std::vector<StepRef>& g = groups[gid[first[lead.b] + lead.s]];
-        bool same = g.size() == g0.size();
-        for (size_t i = 0; same && i < g.size(); ++i) same = g[i].b == g0[i].b && g[i].s == g0[i].s + r.n;
+        const int g = gid[first[lead.b] + lead.s];
+        const StepRef* m = gm.data() + goff[g];
+        bool same = group_size(g) == n0;
+        for (int k = 0; same && k < n0; ++k) same = m[k].b == m0[k].b && m[k].s == m0[k].s + r.n;
         if (!same) break;
-        for (const StepRef& m : g) done[first[m.b] + m.s] = 1;
+        for (int k = 0; k < n0; ++k) done[first[m[k].b] + m[k].s] = 1;
         ++r.n;
       }
       runs.push_back(std::move(r));

@@ -52,6 +52,23 @@ def test_identical_tables_different_lengths_and_empty_requests(mepic, oracle_att
     assert info.total_steps < info.steps_unbatched
 
 
+@pytest.mark.parametrize("kv_dtype,P", [("bf16", 16), ("f8e4m3", 32)])
+def test_many_scattered_unshared_steps(mepic, oracle_attn, kv_dtype, P):
+    """Every other step of three long requests aliases the first request's pages, the steps in between are their
+    own: each request has more unshared one-step stretches than one gather run holds, and its shared steps never
+    form runs longer than one step."""
+    st = W.decode_structure(f"scattered_{kv_dtype}", 95, B=4, Hq=8, Hkv=2, D=128, P=P, theta=5e5, q_dtype="bf16",
+                            kv_dtype=kv_dtype, prefix=4700, n_chunks=0, chunk_tokens=16, pool=1, question=0)
+    aligned, _ = align_with_oracle(st)
+    case = W.assemble(st, aligned)
+    bps = 32 // P
+    for b in range(1, 4):
+        for step in range(b, 140, 2):                     # from a different first step per request
+            case.block_tables[b, step * bps:(step + 1) * bps] = case.block_tables[0, step * bps:(step + 1) * bps]
+    info = check_batched(mepic, oracle_attn, case)
+    assert info.total_steps < info.steps_unbatched
+
+
 @pytest.mark.parametrize("seed", range(6))
 def test_random_structures(mepic, oracle_attn, seed):
     rng = np.random.default_rng(3000 + seed)

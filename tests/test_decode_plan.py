@@ -114,6 +114,15 @@ def test_plan_edge_cases(mepic):
     kv = np.array([192, 170, 0, 33, 192], dtype=np.int32)
     info = check_plan(mepic, bt, kv, 16, 8, 2, mepic.BF16)
     assert info.total_steps < info.steps_unbatched
+    # alternating shared / own steps: more loose steps per request than one gather run holds
+    bt = np.arange(2 * 300, dtype=np.int32).reshape(2, 300)
+    bt[1, 0::4] = bt[0, 0::4]
+    bt[1, 1::4] = bt[0, 1::4]                                 # steps 0, 2, 4, .. (two pages each) coincide
+    plan, info = mepic.decode_plan_build(bt, np.array([4800, 4790], dtype=np.int32), 16, 8, 2, mepic.BF16)
+    _, runs, _, gather, _ = parse(plan, info)
+    n_gather_runs = sum(1 for w in runs if int(w[0]) & 0x200)
+    assert len(gather) == 150 and n_gather_runs == 4          # 75 loose steps per request: 64 + 11
+    check_plan(mepic, bt, np.array([4800, 4790], dtype=np.int32), 16, 8, 2, mepic.BF16)
     # nothing shared: one run per request
     bt = rng.permutation(40).reshape(4, 10).astype(np.int32)
     info = check_plan(mepic, bt, np.array([160, 1, 159, 320], dtype=np.int32), 32, 14, 2, mepic.F8E4M3)
