@@ -62,10 +62,13 @@ def visible_pairs(case) -> int:
 
 
 def time_steps(dc, steps: int, warmup: int, batched: bool = False):
-    """Run warmup + steps calls on torch's current stream. HIP events bracket the timed region and every
-    single step (torch events on the stream the library launches on); a second set of HIP events, handed to
-    the library through timing_start / timing_stop, brackets the main kernel of every call alone.
-    Returns (total ms, list of per-step ms, list of per-step main-kernel ms)."""
+    """Run warmup + 2 x steps calls on torch's current stream. After the warmup, a pass of `steps` calls with
+    events after every step and HIP events, handed to the library through timing_start / timing_stop, that
+    bracket the main kernel of every call alone (on the stream the library launches on). Then the timed pass:
+    the same `steps` calls with nothing between them, bracketed by two events and a synchronize on both sides
+    (an event recorded between calls costs several microseconds of a 60-200 us step, so the pass that carries
+    them is not the one that is timed).
+    Returns (total ms of the timed pass, per-step ms and per-step main-kernel ms of the pass with events)."""
     import torch
     M = dc.M
     run = M.attn_prefill if dc.prefill else M.attn_decode
@@ -86,7 +89,14 @@ def time_steps(dc, steps: int, warmup: int, batched: bool = False):
     dc.params.timing_start = dc.params.timing_stop = None
     per = [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]
     kern = [k0[i].elapsed_ms(k1[i]) for i in range(steps)]
-    return ev[0].elapsed_time(ev[steps]), per, kern
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0.record()
+    for _ in range(steps):
+        run(dc.params)
+    t1.record()
+    torch.cuda.synchronize()
+    return t0.elapsed_time(t1), per, kern
 
 
 def bench_commit(args) -> int:
@@ -200,7 +210,7 @@ def main() -> int:
         dc = DeviceCase(M, c)
         total_ms, per, kern = time_steps(dc, args.steps, args.warmup)
         results[layout] = dict(ms=total_ms / args.steps, min_ms=min(per), kernel=M.last_kernel(),
-                               kernel_ms=sum(kern) / len(kern),
+                               kernel_ms=sum(kern) / len(kern), ms_instr=sum(per) / len(per),
                                pages=c.pages.num_pages, out=dc.out.float().cpu())
         if layout == "shared" and not prefill and M.last_kernel().startswith("decode_mfma"):
             # the same job with one pass over shared pages for several requests (plan built on the host)
@@ -213,7 +223,8 @@ def main() -> int:
                 plan_s = min(plan_s, time.perf_counter() - t0)
             total_ms, per, kern = time_steps(dc, args.steps, args.warmup, batched=True)
             results["shared_batched"] = dict(ms=total_ms / args.steps, min_ms=min(per), kernel=M.last_kernel(),
-                                             kernel_ms=sum(kern) / len(kern), pages=c.pages.num_pages,
+                                             kernel_ms=sum(kern) / len(kern), ms_instr=sum(per) / len(per),
+                                             pages=c.pages.num_pages,
                                              out=dc.out.float().cpu(), plan=info.as_dict(), plan_build_ms=plan_s * 1e3)
         del dc
         torch.cuda.empty_cache()
@@ -281,7 +292,8 @@ def main() -> int:
                             kv_len_mean=float(case.kv_lens.mean()), kv_len_max=int(case.kv_lens.max()),
                             n_q_tokens=case.n_q, algorithmic_bytes=abytes, useful_flops=flops),
                 roofline=roofline, cpu_baseline=cpu,
-                layouts={k: dict(ms_per_step=v["ms"], min_ms=v["min_ms"], kernel_ms=v["kernel_ms"], pages=v["pages"],
+                layouts={k: dict(ms_per_step=v["ms"], ms_per_step_with_events=v["ms_instr"], min_ms=v["min_ms"],
+                                 kernel_ms=v["kernel_ms"], pages=v["pages"],
                                  kernel=v["kernel"], gbs=abytes / (v["ms"] * 1e-3) / 1e9,
                                  **({"plan": v["plan"], "plan_build_ms": v["plan_build_ms"]} if "plan" in v else {}))
                          for k, v in results.items()},
