@@ -274,7 +274,9 @@ int mepic_kv_commit(const mepic_commit_params* params, void* hip_stream);
  * the library, to host memory; the caller copies its first info.n_int32 words to the device and passes
  * that pointer to mepic_attn_decode_batched together with the info struct. A plan is valid for exactly the
  * block tables, kv_lens, head counts and dtype it was built from, on the device that was current when it
- * was built. Supported: (bf16 pages, P = 16) and (fp8 pages, P = 32), D = 128, Hq/Hkv <= 16, no
+ * was built (it is cut for that device's number of waves: MEPIC_ERR_INVALID on another). In a decode loop
+ * that is one plan per decode step, shared by the attention calls of all layers, whose block tables are
+ * the same. Supported: (bf16 pages, P = 16) and (fp8 pages, P = 32), D = 128, Hq/Hkv <= 16, no
  * block_positions / block_valid_mask / interleaved pairing; otherwise MEPIC_ERR_UNSUPPORTED.
  * Errors: MEPIC_ERR_INVALID (null pointers, kv_len beyond the table), MEPIC_ERR_CAPACITY (plan buffer or
  * workspace too small; mepic_decode_plan_capacity gives the worst case for the plan).

@@ -40,6 +40,13 @@
 // (8 bytes per lane and column tile) and the probabilities split into two e4m3 terms (p*4 = hi + lo, 8
 // significant bits together); each step's product goes to a scratch accumulator and enters O scaled by the
 // page's V scale.
+//
+// Batched variant (kBatched): the sequence a KV head's waves share is not the list of requests but a host-built
+// plan of "runs", groups of up to 16/G requests that read identical pages for a number of consecutive steps (the
+// tile's 16 rows then hold G heads of each of them: K is loaded and rotated once for all, every request has its
+// own Q'), plus "gather runs" that collect a request's scattered unshared steps. Its walker prefetches the plan
+// words, page ids, q rows and first K/V loads of the next piece of work while the current one is computed, and the
+// planner, not the kernel, places the cuts between the waves.
 #include <type_traits>
 
 #include "attn_common.h"
