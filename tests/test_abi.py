@@ -91,3 +91,44 @@ def test_commit_shape_errors_are_rejected_before_any_launch(mepic):
         assert lib.mepic_kv_commit(ctypes.byref(cp(**bad)), None) == status, bad
     assert lib.mepic_kv_commit(ctypes.byref(cp(n_tokens=0)), None) == mepic.OK     # nothing to do: ok without pointers
     assert lib.mepic_kv_commit(None, None) == mepic.ERR_INVALID
+
+
+def test_batched_decode_argument_errors_are_rejected_before_any_launch(mepic):
+    import numpy as np
+    lib = mepic.load()
+    bt = np.tile(np.arange(4, dtype=np.int32), (2, 1))
+    kv = np.array([64, 40], dtype=np.int32)
+    plan, info = mepic.decode_plan_build(bt, kv, 16, 8, 2, mepic.BF16)
+    p = params(mepic)
+    need = mepic.attn_decode_batched_workspace_size(p, info)
+    assert need == p.n_q_tokens * p.Hq * info.n_splits * (p.D + 2) * 4
+
+    def status(pp, ii, plan_ptr=None):
+        return lib.mepic_attn_decode_batched(ctypes.byref(pp), plan_ptr, ctypes.byref(ii), None)
+
+    def changed(**over):
+        i2 = mepic.DecodePlanInfo()
+        ctypes.memmove(ctypes.byref(i2), ctypes.byref(info), ctypes.sizeof(info))
+        for k, v in over.items():
+            setattr(i2, k, v)
+        return i2
+    assert status(p, info) == mepic.ERR_INVALID                                   # plan, q, out, pages ... are NULL
+    assert status(params(mepic, B=3, n_q_tokens=3), info) == mepic.ERR_INVALID    # a plan for another batch
+    assert status(params(mepic, Hq=4), info) == mepic.ERR_INVALID                 # ... for another group size
+    assert status(p, changed(n_waves=info.n_waves + 1)) == mepic.ERR_INVALID      # ... cut for another device
+    assert status(p, changed(n_runs=1 << 20)) == mepic.ERR_UNSUPPORTED            # run prefix sums would not fit in LDS
+    assert status(params(mepic, kv_dtype=mepic.F8E4M3, P=16), info) == mepic.ERR_UNSUPPORTED
+    assert status(params(mepic, D=64), info) == mepic.ERR_UNSUPPORTED
+    assert status(params(mepic, flags=mepic.FLAG_FORCE_GENERAL), info) == mepic.ERR_UNSUPPORTED
+    assert lib.mepic_attn_decode_batched(ctypes.byref(p), None, None, None) == mepic.ERR_INVALID
+    # the planner's own checks
+    cap = ctypes.c_size_t()
+    assert lib.mepic_decode_plan_capacity(2, 4, 8, ctypes.byref(cap)) == mepic.ERR_INVALID      # page size
+    assert lib.mepic_decode_plan_capacity(2, 4, 16, None) == mepic.ERR_INVALID
+    out = np.empty(64, dtype=np.int32)
+    i3 = mepic.DecodePlanInfo()
+    args = (bt.ctypes.data, kv.ctypes.data, 2, 4, 16, 8, 2, mepic.BF16, out.ctypes.data)
+    assert lib.mepic_decode_plan_build(*args, ctypes.c_size_t(out.size), ctypes.byref(i3)) == mepic.ERR_CAPACITY
+    assert lib.mepic_decode_plan_build(*args, ctypes.c_size_t(out.size), None) == mepic.ERR_INVALID
+    assert lib.mepic_decode_plan_build(bt.ctypes.data, kv.ctypes.data, 2, 4, 16, 34, 2, mepic.BF16, out.ctypes.data,
+                                       ctypes.c_size_t(out.size), ctypes.byref(i3)) == mepic.ERR_UNSUPPORTED  # G = 17
