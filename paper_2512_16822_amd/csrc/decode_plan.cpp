@@ -67,7 +67,7 @@ int mepic_decode_plan_build(const int32_t* block_tables, const int32_t* kv_lens,
   std::vector<int> nst(B), first(B + 1, 0);
   for (int b = 0; b < B; ++b) {
     const int L = kv_lens[b];
-    if (L < 0 || L > max_blocks * P) return MEPIC_ERR_INVALID;
+    if (L < 0 || (long)L > (long)max_blocks * P) return MEPIC_ERR_INVALID;
     nst[b] = ((L + P - 1) / P + bps - 1) / bps;
     first[b + 1] = first[b] + nst[b];
   }
