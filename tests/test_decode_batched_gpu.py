@@ -98,3 +98,16 @@ def test_full_size_configs_sampled(mepic, oracle_attn, cfg, n_rows):
     rows = sorted({(int(r.integers(case.n_q)), int(r.integers(st.Hq))) for _ in range(n_rows)})
     info = check_batched(mepic, oracle_attn, case, rows=rows)
     assert info.steps_unbatched / info.total_steps > (2.5 if cfg == 2 else 1.6)
+
+
+def test_long_runs_cross_several_page_id_windows(mepic, oracle_attn):
+    """Eight requests of 65 537 slots with one page per logical block: nothing is shared, so each request is one run
+    of 2049 steps and a wave's piece of it spans more blocks than the two windows of page ids it starts with."""
+    st = W.config(4)
+    aligned, _ = align_with_oracle(st)
+    case = W.to_duplicated(W.assemble(st, aligned))
+    r = np.random.default_rng(44)
+    rows = sorted({(int(r.integers(case.n_q)), int(r.integers(st.Hq))) for _ in range(12)})
+    info = check_batched(mepic, oracle_attn, case, rows=rows)
+    assert info.n_runs == st.B and info.total_steps == info.steps_unbatched
+    assert info.total_steps // info.n_waves > 64            # more than 128 blocks per piece
