@@ -33,6 +33,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # FETCH_SIZE x2.000, WRITE_SIZE x1.000). Summaries with the commands are under profiles/.
 MEASURED_TRAFFIC = {
     ("cfg2_llama3_8b_decode_bf16", "duplicated", "decode_mfma_bf16"): int((552122.3 * 2.0 + 3221.6) * 1024),
+    ("cfg4_long_decode_bf16", "duplicated", "decode_mfma_bf16"): int((1050166.1 * 2.0 + 2214.6) * 1024),
+    ("cfg5_mixed_decode_fp8", "duplicated", "decode_mfma_fp8"): int((1113194.1 * 2.0 + 9355.8) * 1024),
+    ("cfg3_question_prefill_bf16", "shared", "prefill_mfma_bf16"): int((320040.3 * 2.0 + 32768.0) * 1024),
 }
 
 
@@ -241,10 +244,12 @@ def main() -> int:
     ms = results[main_layout]["ms"]
     if prefill:
         value, unit, metric = flops / (ms * 1e-3) / 1e12, "TFLOP/s", "fused-RoPE paged prefill attention throughput"
+        roof_layout = main_layout          # bound by the matrix cores: where the pages come from does not matter
         rms = results[roof_layout]["kernel_ms"]
         ach = flops / (rms * 1e-3) / 1e12
+        traffic = MEASURED_TRAFFIC.get((st.name, roof_layout, results[roof_layout]["kernel"]))
         roofline = dict(bound="mfma", achieved=ach, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
-                        frac=ach / MFMA_BF16_PEAK_TFLOPS, traffic=None, layout=roof_layout,
+                        frac=ach / MFMA_BF16_PEAK_TFLOPS, traffic=traffic, layout=roof_layout,
                         kernel=results[roof_layout]["kernel"], kernel_ms=rms, call_ms=results[roof_layout]["ms"])
     else:
         value, unit, metric = abytes / (ms * 1e-3) / 1e9, "GB/s", "fused-RoPE paged decode attention KV throughput"
