@@ -3,8 +3,8 @@
 //   fp8 e4m3 K/V pages of 32 slots with one fp32 scale per page for K and for V (a step = one page).
 // The text below describes the bf16 kernel; the fp8 variant differs where noted at the end.
 //
-// Persistent waves, stream-K over pages. The grid is one workgroup of four waves per compute unit (one
-// wave per SIMD: measured faster than two, whose smaller register budget costs prefetch depth). Workgroup g serves KV head g % Hkv (consecutive workgroups land on consecutive
+// Persistent waves, stream-K over pages. The grid is two workgroups of four waves per compute unit (two waves
+// per SIMD). Workgroup g serves KV head g % Hkv (consecutive workgroups land on consecutive
 // XCDs, so one KV head's pages stay in one XCD's L2). For one KV head the "steps" (two pages = 32
 // slots) of all requests form one sequence of length T; the waves of that head cut it into equal
 // contiguous chunks, regardless of request boundaries. A wave writes one partial (max, sum,
@@ -17,7 +17,8 @@
 //   S^T[32 slots x 16 heads] = Khat[32 x 128] * Q'^T[128 x 16]     2 x 4 v_mfma_f32_16x16x32_bf16
 //   O  [16 heads x 128]     += P[16 x 32 slots] * V[32 x 128]      8     v_mfma_f32_16x16x32_bf16
 //
-// K and V of the next step are in flight while a step is computed.
+// fp8: K and V of the next step are in flight in a second register buffer while a step is computed; bf16 has
+// room for one buffer only (two waves per SIMD leave 256 registers each) and counts on the SIMD's other wave.
 //
 // Rotary embedding without per-key trigonometry: a key at position n0 + s (n0 = first slot of the
 // step) has  q^.k^ = (R(pos_q - n0) q) . (R(s) k).  R(s), s in [0, 32), is a per-lane constant (each
@@ -62,12 +63,15 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kD = 128;
 constexpr int kWaves = 4;             // waves per workgroup
-// Workgroups resident per compute unit. bf16: one (a wave needs more than 256 registers for its two K/V
-// buffers; the kernel sits at the HBM limit anyway). fp8: two (half the bytes per slot make the kernel
-// compute-bound, its buffers are half as large, and the second wave per SIMD fills the issue slots the first
-// leaves while it waits on matrix-core and LDS results).
+// Workgroups resident per compute unit: two, i.e. two waves per SIMD, which fill the issue slots each other leaves
+// while waiting on matrix-core, LDS and memory results. For that a wave has to fit 256 registers: the fp8 kernel
+// does with two register buffers of K and V (the next step's pages in flight while a step is computed); the bf16
+// kernel, whose buffers are twice as large, keeps one (a step's loads are issued, then waited for: the other
+// wave computes meanwhile). Measured against one wave per SIMD with two buffers (bf16): 84 instead of 105 us on
+// the page-sharing layout of the Llama-3-8B decode workload, the same on the layout where every byte comes from
+// HBM, 347 instead of 421 us on the 8 x 65 537-slot workload.
 #ifndef MEPIC_DECODE_WG_PER_CU_BF16
-#define MEPIC_DECODE_WG_PER_CU_BF16 1
+#define MEPIC_DECODE_WG_PER_CU_BF16 2
 #endif
 #ifndef MEPIC_DECODE_WG_PER_CU_FP8
 #define MEPIC_DECODE_WG_PER_CU_FP8 2
@@ -78,10 +82,14 @@ constexpr int kWaves = 4;             // waves per workgroup
 constexpr int wg_per_cu(bool fp8, bool batched = false) {
   return fp8 ? (batched ? MEPIC_DECODE_WG_PER_CU_FP8_BATCHED : MEPIC_DECODE_WG_PER_CU_FP8) : MEPIC_DECODE_WG_PER_CU_BF16;
 }
-#ifndef MEPIC_DECODE_NBUF
-#define MEPIC_DECODE_NBUF 2
+#ifndef MEPIC_DECODE_NBUF_BF16
+#define MEPIC_DECODE_NBUF_BF16 1
 #endif
-constexpr int kNBuf = MEPIC_DECODE_NBUF;          // register buffers of K and V per wave (prefetch depth + 1)
+#ifndef MEPIC_DECODE_NBUF_FP8
+#define MEPIC_DECODE_NBUF_FP8 2
+#endif
+// register buffers of K and V per wave of the plain walker (prefetch depth + 1)
+constexpr int n_buf(bool fp8) { return fp8 ? MEPIC_DECODE_NBUF_FP8 : MEPIC_DECODE_NBUF_BF16; }
 constexpr float kRescaleSlack = 6.f;  // the running maximum may lag the true one by this much (log2 units)
 
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
@@ -466,7 +474,7 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8, kBatched)) void decode
   };
 
   // ---- batched variant: walk the runs of the plan with the metadata of the next piece fetched during the current
-  // one, and the first K/V loads of the next piece issued during the last step of the current one (pieces are
+  // one, and the first K/V loads of the next piece issued right after the last step of the current one (pieces are
   // short — a handful of steps — so their start-up latency would otherwise dominate) ----
   if constexpr (kBatched) {
     const int32_t* runs = a.plan + plan_off_runs(n_items);
@@ -523,17 +531,18 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8, kBatched)) void decode
     bool have_nxt = cur.seg_end < pos_end;
     if (have_nxt) { find(nxt, cur.seg_end, cur.b); stage_a(nxt); }
     stage_b(cur);
-    Frag kbuf[2][2][kNK];
-    VRaw vbuf[2][8];
-    float ks_of[2], vs_of[2];
-    auto issue_pages = [&](auto r_tag, int p0, int p1) __attribute__((always_inline)) {
-      constexpr int rb = decltype(r_tag)::value;
-      if constexpr (kFp8) { ks_of[rb] = a.k_scales[p0]; vs_of[rb] = a.v_scales[p0]; } else { ks_of[rb] = vs_of[rb] = 1.f; }
-      issue_k(kbuf[rb], p0, p1);
-      issue_v(vbuf[rb], p0, p1);
+    // One register buffer of K and V for both formats (measured faster than two for fp8 here, unlike in the plain
+    // walker): a step's loads are issued as soon as the step before it has been computed, also across pieces, so
+    // that they are in flight during the next piece's set-up; the SIMD's other wave computes meanwhile.
+    Frag kbuf[2][kNK];
+    VRaw vbuf[8];
+    float ks_cur = 1.f, vs_cur = 1.f;
+    auto issue_pages = [&](int p0, int p1) __attribute__((always_inline)) {
+      if constexpr (kFp8) { ks_cur = a.k_scales[p0]; vs_cur = a.v_scales[p0]; }
+      issue_k(kbuf, p0, p1);
+      issue_v(vbuf, p0, p1);
     };
-    int par = 0;            // buffer of the current piece's first step
-    bool pre = false;       // that step's loads were issued during the previous piece
+    bool pre = false;       // the current piece's first step was issued during the previous piece
     bool carry_open = false;
     for (;;) {
       const int word0 = uni(cur.w0), R = word0 & 0xff, n_rows = R * G, n_st = cur.n_st;
@@ -561,8 +570,7 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8, kBatched)) void decode
       };
       if (!pre) {
         const int p0 = page(0, 0), p1 = kBps > 1 ? page(0, kBps - 1) : p0;
-        if (par) issue_pages(std::integral_constant<int, 1>{}, p0, p1);
-        else issue_pages(std::integral_constant<int, 0>{}, p0, p1);
+        issue_pages(p0, p1);
       }
       if (have_nxt) stage_b(nxt);  // its plan words were requested a piece ago
       if (!cont) {
@@ -602,32 +610,23 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8, kBatched)) void decode
       q_lds[wave * 4 + 2][lane] = cur.q2; q_lds[wave * 4 + 3][lane] = cur.q3;
       setup_q(my_step * 32);
       pre = false;
-      auto body = [&](auto r_tag, int st) __attribute__((always_inline)) {
-        constexpr int r = decltype(r_tag)::value;
-        if (st + 1 < n_st) {
-          const int p0 = page(st + 1, 0), p1 = kBps > 1 ? page(st + 1, kBps - 1) : p0;
-          issue_pages(std::integral_constant<int, r ^ 1>{}, p0, p1);
-        } else if (have_nxt) {  // the next piece's first step, while this piece's last one is computed
-          const int p0 = __builtin_amdgcn_readlane(nxt.bt0, 0);
-          const int p1 = kBps == 1 ? p0 : (uni(nxt.w0) & kPlanGather) ? __builtin_amdgcn_readlane(nxt.bt1, 0)
-                                                                     : __builtin_amdgcn_readlane(nxt.bt0, 1);
-          issue_pages(std::integral_constant<int, r ^ 1>{}, p0, p1);
-          pre = true;
-        }
+      for (int st = 0; st < n_st; ++st) {
         const int n0 = gather ? 32 * __builtin_amdgcn_readlane(cur.gs, st) : (j0 + kBps * st) * kP;
         if (gather && st > 0) setup_q(n0);
         // a gather step always uses slot table 0 and leaves Q' alone
-        compute(kbuf[r], vbuf[r], n0, gather ? 0 : st, L, gather ? n0 + 32 > L : ragged_end && st == n_st - 1, ks_of[r],
-                vs_of[r]);
-      };
-      int st = 0;
-      if (par) { body(std::integral_constant<int, 1>{}, 0); st = 1; }
-      for (; st + 1 < n_st; st += 2) {
-        body(std::integral_constant<int, 0>{}, st);
-        body(std::integral_constant<int, 1>{}, st + 1);
+        compute(kbuf, vbuf, n0, gather ? 0 : st, L, gather ? n0 + 32 > L : ragged_end && st == n_st - 1, ks_cur, vs_cur);
+        // loads of the step after this one: the next step of this piece, or the first step of the next piece
+        if (st + 1 < n_st) {
+          const int p0 = page(st + 1, 0), p1 = kBps > 1 ? page(st + 1, kBps - 1) : p0;
+          issue_pages(p0, p1);
+        } else if (have_nxt) {
+          const int p0 = __builtin_amdgcn_readlane(nxt.bt0, 0);
+          const int p1 = kBps == 1 ? p0 : (uni(nxt.w0) & kPlanGather) ? __builtin_amdgcn_readlane(nxt.bt1, 0)
+                                                                     : __builtin_amdgcn_readlane(nxt.bt0, 1);
+          issue_pages(p0, p1);
+          pre = true;
+        }
       }
-      if (st < n_st) body(std::integral_constant<int, 0>{}, st);
-      par = (par + n_st) & 1;
 
       carry_open = have_nxt && (uni(nxt.w0) & kPlanContinues) != 0;
       if (!carry_open) {
@@ -713,6 +712,7 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8, kBatched)) void decode
     }
     // Ring of kNBuf register buffers: while a step is computed the K and V of the next kNBuf-1 steps are in
     // flight.
+    constexpr int kNBuf = n_buf(kFp8);
     Frag kbuf[kNBuf][2][kNK];
     VRaw vbuf[kNBuf][8];
     float ks_of[kNBuf], vs_of[kNBuf];  // page scales (fp8), loaded with the step's K and V

@@ -101,11 +101,12 @@ def test_full_size_configs_sampled(mepic, oracle_attn, cfg, n_rows):
 
 
 def test_long_runs_cross_several_page_id_windows(mepic, oracle_attn):
-    """Eight requests of 65 537 slots with one page per logical block: nothing is shared, so each request is one run
-    of 2049 steps and a wave's piece of it spans more blocks than the two windows of page ids it starts with."""
-    st = W.config(4)
+    """Three unshared requests of 46 001 slots with 32 KV heads (few waves per head): each request is one run of
+    1438 steps, and a wave's piece of it spans more blocks than the two windows of page ids it starts with."""
+    st = W.decode_structure("long_unshared", 96, B=3, Hq=32, Hkv=32, D=128, P=16, theta=5e5, q_dtype="bf16",
+                            kv_dtype="bf16", prefix=46000, n_chunks=0, chunk_tokens=16, pool=1, question=0)
     aligned, _ = align_with_oracle(st)
-    case = W.to_duplicated(W.assemble(st, aligned))
+    case = W.assemble(st, aligned)
     r = np.random.default_rng(44)
     rows = sorted({(int(r.integers(case.n_q)), int(r.integers(st.Hq))) for _ in range(12)})
     info = check_batched(mepic, oracle_attn, case, rows=rows)
