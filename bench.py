@@ -210,7 +210,8 @@ def main() -> int:
     layouts = ["shared", "duplicated"] if args.layout == "both" else [args.layout]
     for layout in layouts:
         c = case if layout == "shared" else W.to_duplicated(case)
-        dc = DeviceCase(M, c)
+        # one page per logical block: no page is shared, which the caller tells the library (MEPIC_FLAG_KV_READ_ONCE)
+        dc = DeviceCase(M, c, flags=0 if layout == "shared" else M.FLAG_KV_READ_ONCE)
         total_ms, per, kern = time_steps(dc, args.steps, args.warmup)
         results[layout] = dict(ms=total_ms / args.steps, min_ms=min(per), kernel=M.last_kernel(),
                                kernel_ms=sum(kern) / len(kern), ms_instr=sum(per) / len(per),

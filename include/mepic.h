@@ -166,8 +166,14 @@ typedef enum { MEPIC_F32 = 0, MEPIC_BF16 = 1, MEPIC_F8E4M3 = 2 } mepic_dtype;
 
 enum {
   MEPIC_FLAG_ROPE_INTERLEAVED = 1u, /* pair (x[2i], x[2i+1]) instead of (x[i], x[i+D/2])              */
-  MEPIC_FLAG_FORCE_GENERAL = 2u     /* run the general kernel even where a matrix-core kernel exists
+  MEPIC_FLAG_FORCE_GENERAL = 2u,    /* run the general kernel even where a matrix-core kernel exists
                                        (for tests: both must agree with the oracle)                  */
+  MEPIC_FLAG_KV_READ_ONCE = 4u      /* a hint, never a change of the result: (almost) no page is read by
+                                       more than one request of this call (the pool's unique and logical
+                                       page counts nearly agree). The matrix-core decode kernels then load
+                                       K/V with the non-temporal hint: faster when every byte comes from
+                                       HBM once anyway, slower when requests do share pages, whose reuse
+                                       from the caches it defeats. Other kernels ignore it.            */
 };
 
 typedef struct {

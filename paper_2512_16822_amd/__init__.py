@@ -19,7 +19,7 @@ OK, ERR_INVALID, ERR_NOMEM, ERR_CAPACITY, ERR_UNSUPPORTED, ERR_LAUNCH = 0, -1, -
 SEG_PROMPT, SEG_CHUNK = 0, 1
 BLOCK_PRIVATE, BLOCK_SHARED_HIT, BLOCK_SHARED_NEW = 0, 1, 2
 F32, BF16, F8E4M3 = 0, 1, 2
-FLAG_ROPE_INTERLEAVED, FLAG_FORCE_GENERAL = 1, 2
+FLAG_ROPE_INTERLEAVED, FLAG_FORCE_GENERAL, FLAG_KV_READ_ONCE = 1, 2, 4
 
 EXPORTS = ["mepic_strerror", "mepic_version", "mepic_pool_create", "mepic_pool_destroy", "mepic_align_request",
            "mepic_release_request", "mepic_pool_get_stats", "mepic_pool_lookup_chunk", "mepic_attn_workspace_size",

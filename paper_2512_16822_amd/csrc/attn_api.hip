@@ -118,6 +118,7 @@ int run(const mepic_attn_params* p, void* hip_stream, bool prefill) {
   a.max_blocks = p->max_blocks; a.num_pages = p->num_pages; a.G = p->Hq / p->Hkv;
   a.q_dtype = p->q_dtype; a.kv_dtype = p->kv_dtype;
   a.interleaved = (p->flags & MEPIC_FLAG_ROPE_INTERLEAVED) ? 1 : 0;
+  a.kv_read_once = (p->flags & MEPIC_FLAG_KV_READ_ONCE) ? 1 : 0;
   a.causal = prefill ? 1 : 0;
   a.n_splits = pl.n_splits; a.blocks_per_split = pl.blocks_per_split;
   const double sm = p->sm_scale > 0.f ? (double)p->sm_scale : 1.0 / std::sqrt((double)p->D);

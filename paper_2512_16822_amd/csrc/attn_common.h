@@ -34,6 +34,7 @@ struct AttnArgs {
   int32_t B, n_q, Hq, Hkv, D, P, max_blocks, num_pages, G;
   int32_t q_dtype, kv_dtype;
   int32_t interleaved, causal;
+  int32_t kv_read_once;  // hint: pages are not shared between requests (matrix-core decode: non-temporal loads)
   int32_t n_splits, blocks_per_split;
   float qk_scale_log2;               // sm_scale * log2(e): scores are kept in log2 units
   // Rotary frequencies in turns per position, f_i / (2 pi), split into two floats whose sum carries

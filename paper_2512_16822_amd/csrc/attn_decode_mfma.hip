@@ -116,6 +116,29 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
+// 16- and 8-byte loads of page data, optionally with the non-temporal hint (the line is not kept in the caches):
+// right when every page is read by one request only, wrong when pages are shared between requests.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+template <bool kNT>
+__device__ __forceinline__ uint4 load_page(const uint4* p) {
+  if constexpr (kNT) {
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+    return make_uint4(v[0], v[1], v[2], v[3]);
+  } else {
+    return *p;
+  }
+}
+template <bool kNT>
+__device__ __forceinline__ uint2 load_page(const uint2* p) {
+  if constexpr (kNT) {
+    const u32x2_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x2_t*>(p));
+    return make_uint2(v[0], v[1]);
+  } else {
+    return *p;
+  }
+}
+
 // Wave-uniform read of a read-only int32 input through the scalar unit (s_load): unlike a vector load it
 // does not share the vector-memory counter, so waiting for it never drains the K/V loads in flight.
 typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
@@ -149,7 +172,8 @@ constexpr float kPScaleFp8 = 4.f;     // probabilities (< 2^slack = 64) are mult
 // kBatched: the sequence a KV head's waves cut into chunks is the plan's list of runs (groups of up to 16/G
 // requests stepping through identical pages together) instead of the list of requests; a lane's matrix row then
 // belongs to request row / G of the run.
-template <bool kFp8, bool kBatched>
+// kReadOnce: the caller's hint that pages are not shared between the requests of the call (non-temporal loads).
+template <bool kFp8, bool kBatched, bool kReadOnce = false>
 __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8, kBatched)) void decode_mfma_kernel(const AttnArgs a) {
   constexpr int kP = kFp8 ? 32 : 16;          // slots per page
   constexpr int kBps = kFp8 ? 1 : 2;          // blocks (pages) per step of 32 slots
@@ -258,14 +282,14 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8, kBatched)) void decode
 #pragma unroll
       for (int u = 0; u < 2; ++u)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) kf[u][j].u = kpages[kb + (size_t)(4 * j) * kP + 4 * u];
+        for (int j = 0; j < 2; ++j) kf[u][j].u = load_page<kReadOnce>(&kpages[kb + (size_t)(4 * j) * kP + 4 * u]);
     } else {
       const int pk = (n16 < 8) ? p0 : p1;
       const size_t kb = ((size_t)pk * Hkv + hk) * (kD / 8 * kP) + (size_t)kg * kP + (slot_u0 & 15);
 #pragma unroll
       for (int u = 0; u < 2; ++u)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) kf[u][j].u = kpages[kb + (size_t)(4 * j) * kP + 4 * u];
+        for (int j = 0; j < 4; ++j) kf[u][j].u = load_page<kReadOnce>(&kpages[kb + (size_t)(4 * j) * kP + 4 * u]);
     }
   };
   // V fragments, column tile nt = dim 16nt + n16: bf16: slots 8*(kg&1).. of page kg/2 (16 bytes);
@@ -274,12 +298,12 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8, kBatched)) void decode
     if constexpr (kFp8) {
       const size_t vb = (((size_t)p0 * Hkv + hk) * kD + n16) * 4 + kg;
 #pragma unroll
-      for (int nt = 0; nt < 8; ++nt) vf[nt] = vpages[vb + (size_t)nt * 64];
+      for (int nt = 0; nt < 8; ++nt) vf[nt] = load_page<kReadOnce>(&vpages[vb + (size_t)nt * 64]);
     } else {
       const int pv = (kg < 2) ? p0 : p1;
       const size_t vb = (((size_t)pv * Hkv + hk) * kD + n16) * 2 + (kg & 1);
 #pragma unroll
-      for (int nt = 0; nt < 8; ++nt) vf[nt] = vpages[vb + (size_t)nt * 32];
+      for (int nt = 0; nt < 8; ++nt) vf[nt] = load_page<kReadOnce>(&vpages[vb + (size_t)nt * 32]);
     }
   };
 
@@ -877,8 +901,12 @@ hipError_t launch_decode_mfma(const AttnArgs& a, hipStream_t s) {
   const int n_wg = max(wg_per_cu(fp8) * compute_units() / a.Hkv, 1) * a.Hkv;
   const size_t lds = (size_t)(a.B + 1) * sizeof(int);
   if (a.timing_start) (void)hipEventRecord(reinterpret_cast<hipEvent_t>(a.timing_start), s);
-  if (fp8)
+  if (fp8 && a.kv_read_once)
+    hipLaunchKernelGGL((decode_mfma_kernel<true, false, true>), dim3(n_wg), dim3(64 * kWaves), lds, s, a);
+  else if (fp8)
     hipLaunchKernelGGL((decode_mfma_kernel<true, false>), dim3(n_wg), dim3(64 * kWaves), lds, s, a);
+  else if (a.kv_read_once)
+    hipLaunchKernelGGL((decode_mfma_kernel<false, false, true>), dim3(n_wg), dim3(64 * kWaves), lds, s, a);
   else
     hipLaunchKernelGGL((decode_mfma_kernel<false, false>), dim3(n_wg), dim3(64 * kWaves), lds, s, a);
   hipError_t e = hipGetLastError();

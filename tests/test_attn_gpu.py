@@ -60,6 +60,18 @@ def test_small_decode_all_dtypes(mepic, oracle_attn, kv_dtype, flags):
     check(mepic, oracle_attn, build_case(mepic, small_decode(kv_dtype, P=P)), flags=flags)
 
 
+@pytest.mark.parametrize("kv_dtype,P", [("bf16", 16), ("f8e4m3", 32), ("f32", 16)])
+def test_read_once_hint_changes_no_result(mepic, oracle_attn, kv_dtype, P):
+    """MEPIC_FLAG_KV_READ_ONCE only changes how the matrix-core decode kernels load pages (other kernels ignore it):
+    same bits as without it, on shared pages and on one page per logical block, and within tolerance of the oracle."""
+    case = build_case(mepic, small_decode(kv_dtype, P=P, B=9, n_chunks=(2, 6)))
+    for c in (case, W.to_duplicated(case)):
+        _, plain = check(mepic, oracle_attn, c)
+        want = plain.out.clone()
+        _, hinted = check(mepic, oracle_attn, c, flags=mepic.FLAG_KV_READ_ONCE)
+        assert torch.equal(hinted.out, want)
+
+
 @pytest.mark.parametrize("flags", BOTH_PATHS)
 def test_decode_gqa7_fp8_page32(mepic, oracle_attn, flags):
     """Head shapes of the mixed-length config: 28 query heads on 4 KV heads, page 32, theta 1e6."""
