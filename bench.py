@@ -32,9 +32,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # command (counter readings in KiB, each scaled by what the same counter reads for a 1 GiB device copy:
 # FETCH_SIZE x2.000, WRITE_SIZE x1.000). Summaries with the commands are under profiles/.
 MEASURED_TRAFFIC = {
-    ("cfg2_llama3_8b_decode_bf16", "duplicated", "decode_mfma_bf16"): int((552122.3 * 2.0 + 3221.6) * 1024),
-    ("cfg4_long_decode_bf16", "duplicated", "decode_mfma_bf16"): int((1050166.1 * 2.0 + 2214.6) * 1024),
-    ("cfg5_mixed_decode_fp8", "duplicated", "decode_mfma_fp8"): int((1113194.1 * 2.0 + 9355.8) * 1024),
+    ("cfg2_llama3_8b_decode_bf16", "duplicated", "decode_mfma_bf16"): int((583510.4 * 2.0 + 5221.6) * 1024),
+    ("cfg4_long_decode_bf16", "duplicated", "decode_mfma_bf16"): int((1112407.2 * 2.0 + 4236.3) * 1024),
+    ("cfg5_mixed_decode_fp8", "duplicated", "decode_mfma_fp8"): int((1119965.7 * 2.0 + 9261.2) * 1024),
     ("cfg3_question_prefill_bf16", "shared", "prefill_mfma_bf16"): int((320040.3 * 2.0 + 32768.0) * 1024),
 }
 
