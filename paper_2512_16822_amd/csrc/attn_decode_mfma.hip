@@ -185,6 +185,9 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8, kBatched)) void decode
   // is what limits the loop whenever the pages come from the caches (shared pages) rather than from HBM.
   // bf16 keeps fp32 constants, so two tables are what fits beside the rest in 64 KB of static LDS.
   constexpr int kNV = kFp8 ? 4 : 2;
+  // bf16, plain walker: keys are rotated with two-term dot products (v_dot2_f32_bf16) on (low, high) element pairs,
+  // 9 instead of 14 vector instructions per two pairs; the batched walker, short of registers, keeps fp32 arithmetic
+  constexpr bool kDotRot = !kFp8 && !kBatched;
   typedef typename std::conditional<kFp8, float2, float4>::type RotK;
   __shared__ RotK rotK[kNV * 16][64];  // slot rotation: index v*16 + (u*2 + h)*4 + w
   __shared__ float4 rotS[8][64];       // step rotation R(-32 kNV): index h*4 + w
@@ -241,6 +244,10 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8, kBatched)) void decode
       rotS[idx - kNV * 16][lane] = r;
     } else if constexpr (kFp8) {  // fp8 keys are rotated in packed fp16: {cos pair, sin pair} as two words
       rotK[idx][lane] = make_float2(__uint_as_float(pack_f16x2(r.x, r.z)), __uint_as_float(pack_f16x2(r.y, r.w)));
+    } else if constexpr (kDotRot) {
+      // per pair the two constant words (cos, -sin) and (sin, cos) as packed bf16
+      rotK[idx][lane] = make_float4(__uint_as_float(pack_bf16x2(r.x, -r.y)), __uint_as_float(pack_bf16x2(r.y, r.x)),
+                                    __uint_as_float(pack_bf16x2(r.z, -r.w)), __uint_as_float(pack_bf16x2(r.w, r.z)));
     } else {
       rotK[idx][lane] = r;
     }
@@ -356,6 +363,40 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8, kBatched)) void decode
           }
           sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(klo.hv, bq[h].hv, sc[u], 0, 0, 0);
           sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(khi.hv, bq[h + 2].hv, sc[u], 0, 0, 0);
+        } else if constexpr (kDotRot) {
+#pragma unroll
+          for (int w = 0; w < 4; w += 2) {  // pairs 8h + 2w .. 8h + 2w + 3
+            // Bring the low and the high element of a pair into one word (v_perm_b32); each rotated element is then
+            // one two-term dot product with a constant word, (cos, -sin) or (sin, cos), accumulated in fp32.
+            // Written as one block of eight v_dot2_f32_bf16 followed by four wait states, because another vector
+            // instruction may neither read the result of a dot instruction for three wait states nor rewrite its
+            // register for four, and the compiler places those only around its own builtin — which it lowers to the
+            // accumulating two-operand form plus a move that zeroes the accumulator (no gain). Within the block no
+            // dot reads or rewrites another's result. Early-clobber outputs: none may share a register with an input.
+            const uint32_t la = kf[u][h].w[w], ha = kf[u][h + 2].w[w], lb = kf[u][h].w[w + 1], hb = kf[u][h + 2].w[w + 1];
+            const uint32_t e0 = __builtin_amdgcn_perm(ha, la, 0x05040100u), e1 = __builtin_amdgcn_perm(ha, la, 0x07060302u);
+            const uint32_t e2 = __builtin_amdgcn_perm(hb, lb, 0x05040100u), e3 = __builtin_amdgcn_perm(hb, lb, 0x07060302u);
+            float l0, l1, l2, l3, h0, h1, h2, h3;
+            asm("v_dot2_f32_bf16 %0, %8, %12, 0\n\t"
+                "v_dot2_f32_bf16 %1, %9, %14, 0\n\t"
+                "v_dot2_f32_bf16 %2, %10, %16, 0\n\t"
+                "v_dot2_f32_bf16 %3, %11, %18, 0\n\t"
+                "v_dot2_f32_bf16 %4, %8, %13, 0\n\t"
+                "v_dot2_f32_bf16 %5, %9, %15, 0\n\t"
+                "v_dot2_f32_bf16 %6, %10, %17, 0\n\t"
+                "v_dot2_f32_bf16 %7, %11, %19, 0\n\t"
+                "s_nop 3"
+                : "=&v"(l0), "=&v"(l1), "=&v"(l2), "=&v"(l3), "=&v"(h0), "=&v"(h1), "=&v"(h2), "=&v"(h3)
+                : "v"(e0), "v"(e1), "v"(e2), "v"(e3), "v"(__float_as_uint(r[w].x)), "v"(__float_as_uint(r[w].y)),
+                  "v"(__float_as_uint(r[w].z)), "v"(__float_as_uint(r[w].w)), "v"(__float_as_uint(r[w + 1].x)),
+                  "v"(__float_as_uint(r[w + 1].y)), "v"(__float_as_uint(r[w + 1].z)), "v"(__float_as_uint(r[w + 1].w)));
+            klo.w[w] = pack_bf16x2(l0, l1);
+            klo.w[w + 1] = pack_bf16x2(l2, l3);
+            khi.w[w] = pack_bf16x2(h0, h1);
+            khi.w[w + 1] = pack_bf16x2(h2, h3);
+          }
+          sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(klo.v, bq[h].v, sc[u], 0, 0, 0);
+          sc[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(khi.v, bq[h + 2].v, sc[u], 0, 0, 0);
         } else {
 #pragma unroll
           for (int w = 0; w < 4; ++w) {  // pairs 8h + 2w and 8h + 2w + 1
