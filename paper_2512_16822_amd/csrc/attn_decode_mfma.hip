@@ -46,7 +46,7 @@
 // plan of "runs", groups of up to 16/G requests that read identical pages for a number of consecutive steps (the
 // tile's 16 rows then hold G heads of each of them: K is loaded and rotated once for all, every request has its
 // own Q'), plus "gather runs" that collect a request's scattered unshared steps. Its walker prefetches the plan
-// words, page ids, q rows and first K/V loads of the next piece of work while the current one is computed, and the
+// words, page ids and first K/V loads of the next piece of work while the current one is computed, and the
 // planner, not the kernel, places the cuts between the waves.
 #include <type_traits>
 
@@ -549,8 +549,7 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8, kBatched)) void decode
       int w0, req0, step0, jlast, vreq, vstep, vslot;  // plan words (w0 .. jlast the same in every lane)
       int bt0, bt1, L;                                 // first two windows of page ids of the leader, its kv_len
       int gs;                                          // gather run: lane i holds step i of the piece (bt0 / bt1: its pages)
-      uint4 q0, q1, q2, q3;                            // q of this lane's row: pairs 0-7 and 8-15 low dims, then their high dims
-      int posq;                                        // position of that row's request
+      int posq;                                        // position of the request of this lane's row
     };
     auto find = [&](Meta& m, int pos, int b) __attribute__((always_inline)) {
       while (uni(cum[b + 1]) <= pos) ++b;
@@ -576,12 +575,7 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8, kBatched)) void decode
         m.gs = 0;
       }
       m.L = a.kv_lens[req0];
-      // q and position of the lane's row (rows past the run's requests read request 0's and are zeroed later)
-      const int n_rows = (uni(m.w0) & 0xff) * G;
-      const size_t qrow = ((size_t)m.vreq * a.Hq + (size_t)hk * G + (n16 < n_rows ? n16 % G : 0)) * (kD / 8);
-      const int g0 = kFp8 ? 2 * kg : kg, g1 = kFp8 ? 2 * kg + 1 : 4 + kg;
-      m.q0 = q4[qrow + g0]; m.q1 = q4[qrow + g1]; m.q2 = q4[qrow + 8 + g0]; m.q3 = q4[qrow + 8 + g1];
-      m.posq = a.q_positions[m.vreq];
+      m.posq = a.q_positions[m.vreq];  // rows past the run's requests read request 0's and are zeroed later
     };
     Meta cur, nxt;
     {
@@ -671,8 +665,13 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8, kBatched)) void decode
             qhi[h][e] = x1 * c + x0 * sn;
           }
       };
-      q_lds[wave * 4 + 0][lane] = cur.q0; q_lds[wave * 4 + 1][lane] = cur.q1;
-      q_lds[wave * 4 + 2][lane] = cur.q2; q_lds[wave * 4 + 3][lane] = cur.q3;
+      {  // q of this lane's row into LDS: pairs 0-7 and 8-15 low dims, then their high dims (fetching it a piece
+         // ahead, like the page ids, measured no faster and costs 16 registers)
+        const size_t qrow = ((size_t)my_req * a.Hq + (size_t)hk * G + (row_ok ? g_row : 0)) * (kD / 8);
+        const int g0 = kFp8 ? 2 * kg : kg, g1 = kFp8 ? 2 * kg + 1 : 4 + kg;
+        q_lds[wave * 4 + 0][lane] = q4[qrow + g0]; q_lds[wave * 4 + 1][lane] = q4[qrow + g1];
+        q_lds[wave * 4 + 2][lane] = q4[qrow + 8 + g0]; q_lds[wave * 4 + 3][lane] = q4[qrow + 8 + g1];
+      }
       setup_q(my_step * 32);
       pre = false;
       for (int st = 0; st < n_st; ++st) {
