@@ -157,3 +157,7 @@ def test_commit_then_attend_equals_the_oracle_on_the_original_pages(mepic, oracl
     mepic.kv_commit(p)
     got = dc.run()
     assert np.abs(got - want).max() <= 2e-2
+    # the same right after another commit, with the attention reading the pages past the caches
+    mepic.kv_commit(p)
+    dc.params.flags |= mepic.FLAG_KV_READ_ONCE
+    assert np.array_equal(dc.run(), got)
