@@ -23,8 +23,10 @@
 // Rotary embedding without per-key trigonometry: a key at position n0 + s (n0 = first slot of the
 // step) has  q^.k^ = (R(pos_q - n0) q) . (R(s) k).  R(s), s in [0, 32), is a per-lane constant (each
 // lane always handles the same two slot offsets and the same 16 frequencies) read from LDS, so a key
-// costs one constant 2x2 rotation per element pair; Q' = R(pos_q - n0) q is advanced by a constant rotation
-// (with two tables of slot rotations, R(s) and R(s + 32), only every second step, by R(-64)).
+// costs one constant 2x2 rotation per element pair (in the plain walker two two-term dot products per pair,
+// v_dot2_f32_bf16, on words that v_perm_b32 assembles from the pair's two granules); Q' = R(pos_q - n0) q is
+// advanced by a constant rotation (with two tables of slot rotations, R(s) and R(s + 32), only every second
+// step, by R(-64)).
 //
 // The 16 matrix rows of the QK product are the slots {0-3, 8-11, 16-19, 24-27} (+4 for the second
 // product), which makes each lane end up with the scores of 8 consecutive slots of one page for one
@@ -39,8 +41,8 @@
 // R(-128) once every four steps, because in this variant the advance sits on the critical path of an otherwise
 // memory-bound loop. V is never widened: PV runs on v_mfma_f32_16x16x32_fp8_fp8 with the V bytes as loaded
 // (8 bytes per lane and column tile) and the probabilities split into two e4m3 terms (p*4 = hi + lo, 8
-// significant bits together); each step's product goes to a scratch accumulator and enters O scaled by the
-// page's V scale.
+// significant bits together); the page's V scale rides on the probabilities, O being kept in units of a
+// reference scale that is raised (with a rescale of O) only when a page's scale exceeds it by 1.75 x.
 //
 // Batched variant (kBatched): the sequence a KV head's waves share is not the list of requests but a host-built
 // plan of "runs", groups of up to 16/G requests that read identical pages for a number of consecutive steps (the
