@@ -241,6 +241,9 @@ def make_params(q, out, k_pages, v_pages, block_tables, kv_lens, q_positions, *,
     p.rope_theta, p.sm_scale, p.flags = rope_theta, sm_scale, flags
     if workspace is not None:
         p.workspace, p.workspace_bytes = _p(workspace), workspace.numel() * workspace.element_size()
+    # the struct holds raw device pointers: keep the tensors alive for as long as it is
+    p._tensors = (q, out, k_pages, v_pages, block_tables, kv_lens, q_positions, cu_q_lens, k_scales, v_scales,
+                  block_positions, block_valid_mask, workspace)
     return p
 
 
@@ -320,6 +323,9 @@ def make_commit_params(k_new, v_new, k_pages, v_pages, block_tables, run_request
     p.B, p.n_runs, p.n_tokens, p.Hkv, p.D, p.P = B, run_request.numel(), n_tokens, Hkv, D, v_pages.shape[3]
     p.max_blocks, p.num_pages = max_blocks, k_pages.shape[0]
     p.src_dtype, p.kv_dtype = _dt(k_new), _dt(k_pages)
+    # the struct holds raw device pointers: keep the tensors alive for as long as it is
+    p._tensors = (k_new, v_new, k_pages, v_pages, block_tables, run_request, run_first_slot, cu_run_tokens,
+                  k_scales, v_scales)
     return p
 
 

@@ -292,7 +292,7 @@ def test_fp8_page_scales_spread_over_four_decades(mepic, oracle_attn, order):
 
 
 # ------------------------------------------------------------------ seeded random structures
-@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("seed", range(16))
 def test_random_decode_structures(mepic, oracle_attn, seed):
     """Random batch sizes, group sizes, chunk mixes and lengths on both matrix-core decode kernels."""
     rng = np.random.default_rng(1000 + seed)
@@ -310,7 +310,7 @@ def test_random_decode_structures(mepic, oracle_attn, seed):
     check(mepic, oracle_attn, case, rows=rows, expect_kernel="decode_mfma_fp8" if fp8 else "decode_mfma_bf16")
 
 
-@pytest.mark.parametrize("seed", range(4))
+@pytest.mark.parametrize("seed", range(8))
 def test_random_prefill_structures(mepic, oracle_attn, seed):
     rng = np.random.default_rng(2000 + seed)
     G = int(rng.choice([1, 2, 4, 8]))

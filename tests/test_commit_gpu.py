@@ -152,8 +152,10 @@ def test_commit_then_attend_equals_the_oracle_on_the_original_pages(mepic, oracl
     assert not (np.abs(dc.run() - want).max() <= 2e-2)            # the wipe is visible (NaN or far off)
     i32 = lambda a: torch.tensor(a, dtype=torch.int32, device=dev)
     cu = np.cumsum([0] + [c for _, _, c in runs])
-    p = mepic.make_commit_params(torch.stack(k_rows).to(dev), torch.stack(v_rows).to(dev), dc.k, dc.v, dc.bt,
-                                 i32([r for r, _, _ in runs]), i32([f for _, f, _ in runs]), i32(cu))
+    # the params struct holds raw pointers: keep every tensor it points at alive for as long as it is used
+    held = (torch.stack(k_rows).to(dev), torch.stack(v_rows).to(dev), i32([r for r, _, _ in runs]),
+            i32([f for _, f, _ in runs]), i32(cu))
+    p = mepic.make_commit_params(held[0], held[1], dc.k, dc.v, dc.bt, held[2], held[3], held[4])
     mepic.kv_commit(p)
     got = dc.run()
     assert np.abs(got - want).max() <= 2e-2

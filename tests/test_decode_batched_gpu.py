@@ -69,7 +69,7 @@ def test_many_scattered_unshared_steps(mepic, oracle_attn, kv_dtype, P):
     assert info.total_steps < info.steps_unbatched
 
 
-@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("seed", range(12))
 def test_random_structures(mepic, oracle_attn, seed):
     rng = np.random.default_rng(3000 + seed)
     fp8 = bool(seed & 1)
