@@ -505,7 +505,8 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8, kBatched)) void decode
         for (int nt = 0; nt < 8; ++nt) o[nt] *= f;
         v_ref = vsc;
       }
-      const float ps = v_ref > 0.f ? kPScaleFp8 * vsc / v_ref : 0.f;  // a zero scale means an all-zero page
+      // (one v_rcp_f32, good to an ulp, instead of a correctly rounded division: this runs every step)
+      const float ps = v_ref > 0.f ? kPScaleFp8 * vsc * __builtin_amdgcn_rcpf(v_ref) : 0.f;  // a zero scale means an all-zero page
       uint32_t hi[2], lo[2];
 #pragma unroll
       for (int w = 0; w < 2; ++w) {
