@@ -182,7 +182,8 @@ typedef struct {
   const void* k_pages;              /* device, K page layout above, kv_dtype, UN-rotated              */
   const void* v_pages;              /* device, V page layout above, kv_dtype                          */
   const float* k_scales;            /* device [num_pages] fp32; required iff kv_dtype == F8E4M3:      */
-  const float* v_scales;            /*   stored value = e4m3fn code * scale of its page               */
+  const float* v_scales;            /*   stored value = e4m3fn code * scale of its page; scales are
+                                       magnitudes (amax / 448): finite and >= 0                       */
   const int32_t* block_tables;      /* device [B][max_blocks] physical page ids in [0, num_pages)     */
   const int32_t* kv_lens;           /* device [B] valid KV slots per request (<= max_blocks * P)      */
   const int32_t* q_positions;       /* device [n_q_tokens] absolute position of each query token      */
