@@ -183,7 +183,7 @@ def main() -> int:
     import torch
     import paper_2512_16822_amd as M
     import workloads as W
-    from harness import DeviceCase, align_with_library
+    from paper_2512_16822_amd.device_case import DeviceCase, align_with_library
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     M.load()
