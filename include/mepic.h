@@ -214,6 +214,20 @@ int mepic_attn_workspace_size(const mepic_attn_params* params, int is_prefill, s
 /* Decode: one query token per request attends to all of the request's valid slots (§3.3.3). */
 int mepic_attn_decode(const mepic_attn_params* params, void* hip_stream);
 
+/*
+ * mepic_attn_decode for callers that cannot supply (or allocate) a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid allocation. The split-K partials go to a fixed array of
+ * MEPIC_NOALLOC_SCRATCH_BYTES inside the library's device image (one copy per GPU, held until the process
+ * ends); params->workspace and workspace_bytes are ignored. Same kernels, same result bit for bit as
+ * mepic_attn_decode with a workspace. Calls no hipMalloc / hipFree nor any allocating routine.
+ * MEPIC_ERR_CAPACITY when mepic_attn_workspace_size for these shapes exceeds MEPIC_NOALLOC_SCRATCH_BYTES
+ * (the BASELINE-sized decode batches need 17-32 MB); otherwise the errors of mepic_attn_decode.
+ * All calls on one GPU share that GPU's array: two such calls that overlap in time on one GPU (different
+ * streams, different threads) race; calls on one stream are ordered and safe.
+ */
+#define MEPIC_NOALLOC_SCRATCH_BYTES (48u << 20)
+int mepic_attn_decode_noalloc(const mepic_attn_params* params, void* hip_stream);
+
 /* Prefill of question tokens: the tokens cu_q_lens[b]..cu_q_lens[b+1] of request b attend causally,
  * by absolute position, to the request's slots; their own K/V are already committed to the request's
  * private pages (§3.3.2 precedes §3.3.3). */

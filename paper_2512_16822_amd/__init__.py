@@ -20,12 +20,13 @@ SEG_PROMPT, SEG_CHUNK = 0, 1
 BLOCK_PRIVATE, BLOCK_SHARED_HIT, BLOCK_SHARED_NEW = 0, 1, 2
 F32, BF16, F8E4M3 = 0, 1, 2
 FLAG_ROPE_INTERLEAVED, FLAG_FORCE_GENERAL, FLAG_KV_READ_ONCE = 1, 2, 4
+NOALLOC_SCRATCH_BYTES = 48 << 20
 
 EXPORTS = ["mepic_strerror", "mepic_version", "mepic_pool_create", "mepic_pool_destroy", "mepic_align_request",
            "mepic_release_request", "mepic_pool_get_stats", "mepic_pool_lookup_chunk", "mepic_attn_workspace_size",
            "mepic_attn_decode", "mepic_attn_prefill", "mepic_last_kernel", "mepic_kv_commit",
            "mepic_decode_plan_capacity", "mepic_decode_plan_build", "mepic_attn_decode_batched_workspace_size",
-           "mepic_attn_decode_batched"]
+           "mepic_attn_decode_batched", "mepic_attn_decode_noalloc"]
 
 
 class MepicError(RuntimeError):
@@ -112,6 +113,7 @@ def load() -> ctypes.CDLL:
                                               ctypes.POINTER(ctypes.c_size_t)]
     lib.mepic_attn_decode.argtypes = [ctypes.POINTER(AttnParams), ctypes.c_void_p]
     lib.mepic_attn_prefill.argtypes = [ctypes.POINTER(AttnParams), ctypes.c_void_p]
+    lib.mepic_attn_decode_noalloc.argtypes = [ctypes.POINTER(AttnParams), ctypes.c_void_p]
     lib.mepic_kv_commit.argtypes = [ctypes.POINTER(CommitParams), ctypes.c_void_p]
     lib.mepic_decode_plan_capacity.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                                ctypes.POINTER(ctypes.c_size_t)]
@@ -266,6 +268,13 @@ def attn_decode(params: AttnParams, stream=None) -> None:
     rc = load().mepic_attn_decode(ctypes.byref(params), _stream_handle(stream))
     if rc != OK:
         raise MepicError(rc, "mepic_attn_decode")
+
+
+def attn_decode_noalloc(params: AttnParams, stream=None) -> None:
+    """mepic_attn_decode_noalloc on `stream` (default: torch's current stream); params.workspace is ignored."""
+    rc = load().mepic_attn_decode_noalloc(ctypes.byref(params), _stream_handle(stream))
+    if rc != OK:
+        raise MepicError(rc, "mepic_attn_decode_noalloc")
 
 
 def attn_prefill(params: AttnParams, stream=None) -> None:

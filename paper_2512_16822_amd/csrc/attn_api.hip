@@ -2,11 +2,36 @@
 // rotary frequency table, and dispatch to the kernels. No device memory is allocated here.
 #include <cmath>
 #include <cstring>
+#include <mutex>
 
 #include "attn_common.h"
 
+// Scratch of mepic_attn_decode_noalloc: the split-K partials and their metadata live here instead of in a
+// caller-supplied workspace. Every GPU the library runs on holds its own copy of the array, at its own address,
+// until the process ends. In host code the name below is only a handle for hipGetSymbolAddress: the device
+// address it yields (kept per device in g_scratch_ptr) is what kernels and runtime calls get.
+static __device__ __align__(256) unsigned char scratch[MEPIC_NOALLOC_SCRATCH_BYTES];
+
 namespace mepic {
 namespace {
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (looked up once per device, with that device current).
+int scratch_of_current_device(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MEPIC_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return MEPIC_ERR_LAUNCH;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return MEPIC_OK;
+}
 
 thread_local const char* g_last_kernel = "";
 
@@ -59,14 +84,15 @@ Plan make_plan(const mepic_attn_params* p, bool prefill) {
 
   if (prefill && plain && mfma_bf16 && prefill_mfma_rows_per_workgroup() % G == 0) {
     // Matrix-core prefill: one workgroup per (request, KV head, tile of 256 query rows); no split over KV, the
-    // output is written directly.
+    // output is written directly. The workspace holds the rotary table.
     pl.kernel = K_PREFILL_MFMA_BF16;
     const int max_q = p->max_q_len > 0 && p->max_q_len < p->n_q_tokens ? p->max_q_len : p->n_q_tokens;
     const int tok_per_wg = prefill_mfma_rows_per_workgroup() / G;
     pl.n_splits = (max_q + tok_per_wg - 1) / tok_per_wg;
     if (pl.n_splits < 1) pl.n_splits = 1;
     pl.blocks_per_split = n_blocks;
-    pl.workspace_bytes = 0;
+    // the per-position rotary table the call builds for itself: 32 entries of 16 bytes per position
+    pl.workspace_bytes = (size_t)prefill_mfma_table_positions(n_blocks * p->P) * 32 * sizeof(float4);
     return pl;
   }
 
@@ -144,9 +170,8 @@ int run(const mepic_attn_params* p, void* hip_stream, bool prefill) {
       break;
     case K_PREFILL_MFMA_BF16:
       g_last_kernel = "prefill_mfma_bf16";
-      mark(a.timing_start, s);
+      a.rope_table = reinterpret_cast<float4*>(p->workspace);
       e = launch_prefill_mfma_bf16(a, s);
-      mark(a.timing_stop, s);
       break;
     default:
       g_last_kernel = "general";
@@ -240,6 +265,23 @@ int mepic_attn_workspace_size(const mepic_attn_params* params, int is_prefill, s
 
 int mepic_attn_decode(const mepic_attn_params* params, void* hip_stream) {
   return mepic::run(params, hip_stream, false);
+}
+
+int mepic_attn_decode_noalloc(const mepic_attn_params* params, void* hip_stream) {
+  if (!params) return MEPIC_ERR_INVALID;
+  const int rc = mepic::check_shapes(params, false);
+  if (rc != MEPIC_OK) return rc;
+  // same plan as mepic_attn_decode, so the same partials; they must fit the fixed array
+  if (mepic::make_plan(params, false).workspace_bytes > (size_t)MEPIC_NOALLOC_SCRATCH_BYTES) return MEPIC_ERR_CAPACITY;
+  void* ptr = nullptr;
+  const int rs = mepic::scratch_of_current_device(&ptr);
+  if (rs != MEPIC_OK) return rs;
+  // Nothing in the array has to start at zero: the kernels write every partial and every metadata word the merge
+  // kernel reads, so the contents a previous call left behind are never looked at.
+  mepic_attn_params p = *params;
+  p.workspace = ptr;
+  p.workspace_bytes = (size_t)MEPIC_NOALLOC_SCRATCH_BYTES;
+  return mepic::run(&p, hip_stream, false);
 }
 
 int mepic_attn_prefill(const mepic_attn_params* params, void* hip_stream) {
