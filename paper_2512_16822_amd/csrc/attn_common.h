@@ -31,6 +31,7 @@ struct AttnArgs {
   void* timing_stop;
   int32_t* part_meta;                // stream-K decode: steps before each request [B+1], then the chunk
   const int32_t* plan;               // batched decode: the plan blob (device), see decode_plan.h
+  float4* rope_table;                // matrix-core prefill: per-position cos/sin entries (built by the call itself)
   int32_t B, n_q, Hq, Hkv, D, P, max_blocks, num_pages, G;
   int32_t q_dtype, kv_dtype;
   int32_t interleaved, causal;
@@ -72,6 +73,7 @@ hipError_t launch_combine(const AttnArgs& a, hipStream_t s);
 hipError_t launch_decode_mfma(const AttnArgs& a, hipStream_t s);  // bf16 or fp8 pages; includes its merge kernel
 hipError_t launch_prefill_mfma_bf16(const AttnArgs& a, hipStream_t s);  // n_splits = query tiles per request
 int prefill_mfma_rows_per_workgroup();
+int prefill_mfma_table_positions(int max_kv_len);                    // positions its rotary table covers (16 bytes x 32 each)
 void decode_mfma_plan(int B, int Hkv, int max_kv_len, bool fp8, int* max_splits, int* min_chunk);
 int decode_mfma_waves_per_head(int Hkv, bool fp8);                   // waves that share one KV head's steps
 hipError_t launch_decode_mfma_batched(const AttnArgs& a, int n_runs, hipStream_t s);  // plan-driven variant
