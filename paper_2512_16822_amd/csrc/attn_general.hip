@@ -75,6 +75,7 @@ __global__ __launch_bounds__(kThreads) void attn_general_kernel(const AttnArgs a
   __shared__ float qhat[GM * 2 * kMaxHalfD];  // [G][D], rotated, pre-multiplied by the score scale
   __shared__ float sc[GM * kThreads];         // [G][256] scores, then probabilities, of the tile
   __shared__ float red[kWaves * GM];
+  __shared__ unsigned char took[kThreads];    // does the slot of the tile take part (valid, visible, below kv_len)?
   __shared__ int s_req;
 
   // which request owns this query token
@@ -196,7 +197,8 @@ __global__ __launch_bounds__(kThreads) void attn_general_kernel(const AttnArgs a
       sc[g * kThreads + tid] = p;
       s[g] = p;
     }
-    __syncthreads();  // red fully read, sc fully written
+    took[tid] = take ? 1 : 0;
+    __syncthreads();  // red fully read, sc and took fully written
     _Pragma("unroll") for (int g = 0; g < GM; ++g) {
       if (g >= G) continue;
       const float ws = wave_sum(s[g]);
@@ -225,8 +227,9 @@ __global__ __launch_bounds__(kThreads) void attn_general_kernel(const AttnArgs a
 #pragma unroll
         for (int e = 0; e < X; ++e) {
           const int rel = jb * P + c * X + e;  // slot index inside the tile
-          // slots at or past kv_len may hold anything (even NaN): never let them into the sum
-          const float vv = (n0 + rel < n_end) ? v[e] * vsc : 0.f;
+          // a slot that does not take part (at or past kv_len, a pad slot the valid mask drops, a key the causal rule
+          // hides) may hold anything, even NaN, and 0 x NaN is NaN: never let its V into the sum
+          const float vv = took[rel] ? v[e] * vsc : 0.f;
           _Pragma("unroll") for (int g = 0; g < GM; ++g)
             if (g < G) acc[g] += sc[g * kThreads + rel] * vv;
         }

@@ -3,14 +3,14 @@
 //
 // One workgroup of 8 waves serves 256 query rows (a row = one query token x one of the G query heads
 // that share a KV head; 256/G tokens) of one (request, KV head) and walks the request's KV in tiles of
-// 64 slots (4 pages). The vector pipe, not the matrix pipe, is what a tile waits for, so everything is
-// arranged to need few vector instructions per tile:
-//   stage   every thread pulls two 16-byte granules of K from the pages and rotates them in registers at the
-//           slot's absolute position with cos/sin read from a per-position table (built once per call by
-//           rope_table_kernel: no trigonometry and no rotation state to advance in the loop), then writes them
-//           to LDS as bf16 in matrix-operand order. The rotated tile is shared by all 256 rows, so the rotation
-//           costs 1/256 per row. V never passes through registers: the four page-heads of the tile are copied
-//           from HBM straight into LDS (global_load_lds_dwordx4) as they are.
+// 64 slots (4 pages). What a tile costs is not matrix-pipe time but the waits of its two waves per SIMD (for
+// global loads, for LDS operands, for each other at the barrier), so the kernel is arranged around those:
+//   stage   every thread pulls two 16-byte granules of K and two of V from the pages (issued a whole tile before
+//           they are needed) and rotates K in registers at the slot's absolute position with cos/sin read from a
+//           per-position table (built once per call by rope_table_kernel: no trigonometry and no rotation state to
+//           advance in the loop), then writes both to LDS: K as bf16 in matrix-operand order, V as it lies in the
+//           page (16-byte pieces swapped pairwise so that operand reads hit every bank once). The rotated tile is
+//           shared by all 256 rows, so the rotation costs 1/256 per row.
 //   QK      S^T[64 slots x 32 rows] per wave = Khat (LDS) x Qhat^T (registers), v_mfma_f32_32x32x16_bf16.
 //           Transposed so that a lane owns one query row: row sums are register-local. The accumulator starts
 //           at minus the row's reference maximum, so the scores come out of the products already shifted.
@@ -18,9 +18,13 @@
 //           probabilities of eight consecutive slots of one page: exactly the 16-byte piece of a V page row.
 //   softmax online; the reference maximum is a lower bound raised only when a probability would get huge (the
 //           test is on the row sum that is needed anyway), causal / length mask only on tiles that need it.
-//   PV      O^T[128 x 32 rows] += V^T (LDS, as stored in the page) x P^T (the S^T registers, packed in place).
-// LDS tiles are double-buffered: one barrier per tile, the next tile's global loads are in flight during
-// the products.
+//   PV      O^T[128 x 32 rows] += V^T (LDS) x P^T (the S^T registers, packed in place).
+// Matrix operands come from LDS through a ring of eight registers quadruples: the read for the product eight places
+// ahead is issued right behind each product, so products do not wait for LDS. Three LDS tile buffers and ONE
+// barrier per tile; the waves of a SIMD belong to two groups that stage the next tile before, respectively after,
+// that barrier, which keeps them one segment apart. Page ids come 64 at a time through a vector load and
+// v_readlane: nothing in the loop uses the scalar-memory counter the LDS waits share.
+#include <mutex>
 #include <type_traits>
 
 #include "attn_common.h"
@@ -53,16 +57,9 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
+typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;  // scalar loads: set-up only, never in the loop
 __device__ __forceinline__ int sload(const int32_t* p, size_t idx) { return ((const_i32_ptr)(uintptr_t)p)[idx]; }
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
-
-// 16 bytes per lane from global memory straight into LDS: lane i's piece lands at lds_base + 16 i (lds_base is
-// wave-uniform). Counted by vmcnt like any other vector-memory load; the data never touches a register.
-__device__ __forceinline__ void load_to_lds(const uint4* src, uint4* lds_base) {
-  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                   (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
-}
 
 // Per-position rotary table: for position p and frequency pair (i0, i0 + 1), i0 = 8 pc + 2 j, one 16-byte entry
 // {cos(p f_i0), sin(p f_i0), cos(p f_i0+1), sin(p f_i0+1)} at entry index
@@ -85,14 +82,23 @@ __global__ __launch_bounds__(256) void rope_table_kernel(const AttnArgs a, int n
 
 // LDS tile layouts (per buffer):
 //   K: [16 chunks of 8 dims][64 slots] granules of 16 bytes -> granule (c, s) at c*64 + s, rotated, bf16
-//   V: the tile's four page-heads as they lie in HBM, [4 pages][128 dims][2 halves of 8 slots] granules
+//   V: the tile's four page-heads, [4 pages][128 dims][2 halves of 8 slots] granules, the two halves of a dim
+//      swapped when bit 3 of the dim is set (16 consecutive lanes of an operand read then cover all 64 banks)
+constexpr int kNBuf = 3;
+// Workgroup barrier that orders LDS traffic only: global loads issued before it stay in flight across it.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
 struct __align__(16) Tile {
   uint4 k[16 * kTile];
   uint4 v[4 * kD * 2];
 };
 
 __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_bf16_kernel(const AttnArgs a) {
-  __shared__ Tile tiles[2];
+  extern __shared__ uint4 lds_all[];
+  Tile* const tiles = reinterpret_cast<Tile*>(lds_all);   // kNBuf tiles
   const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
   const int l32 = lane & 31, half = lane >> 5;
   const int G = a.G, Hkv = a.Hkv;
@@ -167,15 +173,12 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_bf16_kernel(const At
   const uint4* vpages = reinterpret_cast<const uint4*>(a.v_pages);
   const float4* table = a.rope_table + rope_entry(s_st, pc, 0);   // + 2048 entries per tile, + 64 per j
   const size_t bt_row = (size_t)b * a.max_blocks;
-  // the four pages of tile t (block indices clamped to the request's last block; clamped slots are masked)
-  auto tile_page = [&](int t, int k) { return sload(a.block_tables, bt_row + min(4 * t + k, max(n_blocks - 1, 0))); };
-
-  // V of a tile goes from the pages straight into LDS: wave w copies half w%2 (64 dims = 2 KB) of page-head w/2
+  // V of a tile: wave w moves half w%2 (64 dims = 2 KB) of page-head w/2
   const int v_page_sel = wave >> 1, v_gran0 = (wave & 1) * 128 + lane;
 
-  Frag gk[2];
+  Frag gk[2], gv[2];
   float4 gt[4];
-  auto load_tile = [&](int t, int buf, int p0, int p1, int p2, int p3) __attribute__((always_inline)) {
+  auto load_tile = [&](int t, int p0, int p1, int p2, int p3) __attribute__((always_inline)) {
     const int pg_k = (s_st < 32) ? (s_st < 16 ? p0 : p1) : (s_st < 48 ? p2 : p3);
     const size_t kb = ((size_t)pg_k * Hkv + hk) * (kD / 8 * kP) + (size_t)pc * kP + (s_st & 15);
     gk[0].u = kpages[kb];
@@ -184,12 +187,12 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_bf16_kernel(const At
     for (int j = 0; j < 4; ++j) gt[j] = table[(size_t)t * 2048 + j * 64];
     const int pg_v = v_page_sel < 2 ? (v_page_sel == 0 ? p0 : p1) : (v_page_sel == 2 ? p2 : p3);  // wave-uniform
     const uint4* vsrc = vpages + ((size_t)pg_v * Hkv + hk) * (kD * 2) + v_gran0;
-    uint4* vdst = &tiles[buf].v[v_page_sel * (kD * 2) + (wave & 1) * 128];
-    load_to_lds(vsrc, vdst);
-    load_to_lds(vsrc + 64, vdst + 64);
+    gv[0].u = vsrc[0];
+    gv[1].u = vsrc[64];
   };
-  // rotate the staged K granules at position (tile start + s_st), write them into LDS buffer `buf`; make sure this
-  // wave's share of the tile's V has landed in LDS and holds no garbage past kv_len
+  // rotate the staged K granules at position (tile start + s_st) and write them into LDS buffer `buf`; V goes there as
+  // loaded, except that slots at or past kv_len, which may hold anything (NaN included: 0 x NaN would poison the
+  // row), are zeroed
   auto stage_tile = [&](int buf, int n0) __attribute__((always_inline)) {
     Frag klo, khi;
 #pragma unroll
@@ -203,26 +206,19 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_bf16_kernel(const At
     }
     tiles[buf].k[pc * kTile + s_st] = klo.u;
     tiles[buf].k[(pc + 8) * kTile + s_st] = khi.u;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the direct-to-LDS copies of V are not tied to any register
-    if (n0 + kTile > L) {
-      // Slots at or past kv_len may hold anything, NaN included, and 0 x NaN would poison the row: zero them.
-      // Each wave patches the 2 KB it copied itself (two granules per lane: dim, half of the page's slots).
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int gi = v_gran0 + 64 * i;              // granule of the page-head: dim gi / 2, slots 8 (gi & 1)..
-        const int nbase = n0 + v_page_sel * kP + 8 * (gi & 1);
-        if (nbase + 8 > L) {
-          uint4* cell = &tiles[buf].v[v_page_sel * (kD * 2) + gi];
-          Frag x;
-          x.u = *cell;
+    for (int i = 0; i < 2; ++i) {
+      const int gi = v_gran0 + 64 * i;              // granule of the page-head: dim gi / 2, slots 8 (gi & 1)..
+      const int nbase = n0 + v_page_sel * kP + 8 * (gi & 1);
+      Frag x = gv[i];
+      if (nbase + 8 > L) {
 #pragma unroll
-          for (int w = 0; w < 4; ++w) {
-            const int n = nbase + 2 * w;
-            x.w[w] &= (n < L ? 0x0000ffffu : 0u) | (n + 1 < L ? 0xffff0000u : 0u);
-          }
-          *cell = x.u;
+        for (int w = 0; w < 4; ++w) {
+          const int n = nbase + 2 * w;
+          x.w[w] &= (n < L ? 0x0000ffffu : 0u) | (n + 1 < L ? 0xffff0000u : 0u);
         }
       }
+      tiles[buf].v[v_page_sel * (kD * 2) + (gi ^ ((gi >> 4) & 1))] = x.u;
     }
   };
 
@@ -238,33 +234,70 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_bf16_kernel(const At
 #pragma unroll
   for (int e = 0; e < 16; ++e) negm[e] = 0.f;
 
-  if (n_tiles > 0) load_tile(0, 0, tile_page(0, 0), tile_page(0, 1), tile_page(0, 2), tile_page(0, 3));
-  int np0 = tile_page(1, 0), np1 = tile_page(1, 1), np2 = tile_page(1, 2), np3 = tile_page(1, 3);
+  // Page ids of 16 tiles at a time: lane i of bt_cur holds the page of block 64 * bt_win + i (clamped to the
+  // request's last block), bt_nxt the 64 after those; a tile reads its four ids with v_readlane. Vector loads on
+  // purpose: scalar loads share a counter with the LDS reads and return out of order, so one in flight would turn
+  // every wait for an LDS operand into a full drain.
+  auto bt_load = [&](int win) { return a.block_tables[bt_row + min(64 * win + lane, max(n_blocks - 1, 0))]; };
+  int bt_win = 0, bt_cur = 0, bt_nxt = 0;
+  if (n_tiles > 0) {   // (a request without visible slots has nothing to read, possibly not even a block table)
+    bt_cur = bt_load(0);
+    bt_nxt = bt_load(1);
+  }
+  auto pages_of = [&](int t, int& p0, int& p1, int& p2, int& p3) __attribute__((always_inline)) {  // non-decreasing t
+    if ((t >> 4) != bt_win) {
+      ++bt_win;
+      bt_cur = bt_nxt;
+      bt_nxt = bt_load(bt_win + 1);
+    }
+    const int l0 = (4 * t) & 63;
+    p0 = __builtin_amdgcn_readlane(bt_cur, l0);
+    p1 = __builtin_amdgcn_readlane(bt_cur, l0 + 1);
+    p2 = __builtin_amdgcn_readlane(bt_cur, l0 + 2);
+    p3 = __builtin_amdgcn_readlane(bt_cur, l0 + 3);
+  };
+  int np0 = 0, np1 = 0, np2 = 0, np3 = 0;
 
   // Matrix row m of a 32-slot block holds slot (m & 16) + 8 * bit2(m) + 4 * bit3(m) + (m & 3) of the block: a lane
   // of the score tile (row l32, half) then owns, in accumulator order, slots 8 half .. 8 half + 7 of the block's first
   // page and the same of its second page.
   const int k_read = (l32 & 16) + ((l32 & 4) << 1) + ((l32 & 8) >> 1) + (l32 & 3);
 
-  auto tile_step = [&](int t, auto buf_tag) __attribute__((always_inline)) {
-    constexpr int buf = decltype(buf_tag)::value;  // compile-time, so that LDS addresses fold into offsets
+  auto tile_step = [&](int t, int buf) __attribute__((always_inline)) {
     const int n0 = t * kTile;
-    stage_tile(buf, n0);
-    __syncthreads();
-    if (t + 1 < n_tiles) load_tile(t + 1, buf ^ 1, np0, np1, np2, np3);
-    np0 = tile_page(t + 2, 0); np1 = tile_page(t + 2, 1); np2 = tile_page(t + 2, 2); np3 = tile_page(t + 2, 3);
 
     const bool need_mask = n0 + kTile - 1 > min(pos_min, L - 1);  // some row cannot see the whole tile
+    // Operand ring: the LDS read of the operand that the product eight places later needs is issued right after
+    // a product has consumed the ring entry, so that no product waits for LDS.
+    Frag ring[8];
+    const uint4* kt = tiles[buf].k + half * kTile + k_read;
+    const uint4* vt = tiles[buf].v + l32 * 2 + (half ^ ((l32 >> 3) & 1));
+#pragma unroll
+    for (int i = 0; i < 8; ++i) ring[i].u = kt[2 * i * kTile];
+    floatx16 sc2[2];
+    sc2[0] = negm;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      sc2[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i].v, bq[i].v, sc2[0], 0, 0, 0);
+      ring[i].u = kt[2 * i * kTile + 32];
+    }
+    sc2[1] = negm;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      sc2[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i].v, bq[i].v, sc2[1], 0, 0, 0);
+      ring[i].u = vt[((i >> 2) * kD + 32 * (i & 3)) * 2];          // pages 0, 1 of the tile
+    }
+    // pin the order: eight reads, then sixteen times (product, read of the operand eight products ahead)
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int sb = 0; sb < 2; ++sb) {
-      // S^T block: accumulator element e of lane (row l32, half) is slot n0 + 32sb + 16(e>>3) + 8half + (e&7)
-      floatx16 sc = negm;
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        Frag ka;
-        ka.u = tiles[buf].k[(2 * ks + half) * kTile + 32 * sb + k_read];
-        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka.v, bq[ks].v, sc, 0, 0, 0);
-      }
+      floatx16 sc = sc2[sb];
       if (need_mask) {
 #pragma unroll
         for (int e = 0; e < 16; ++e)
@@ -277,8 +310,6 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_bf16_kernel(const At
         p[e] = __builtin_amdgcn_exp2f(sc[e]);
         psum += p[e];
       }
-      // Raise the reference maximum only when a probability got huge (or overflowed), or on the first visible slots of
-      // the row; both lanes of a row (l32, half 0/1) must agree on it, so the decision and the new value are common.
       if (__any(!(psum <= kBig) || m_run == -INFINITY)) {
         float mx = sc[0];
 #pragma unroll
@@ -298,6 +329,10 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_bf16_kernel(const At
             for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
 #pragma unroll
           for (int e = 0; e < 16; ++e) negm[e] = -m_run;
+          if (sb == 0) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) sc2[1][e] -= delta;   // the second block's scores were shifted by the old reference
+          }
           psum = 0.f;
 #pragma unroll
           for (int e = 0; e < 16; ++e) {
@@ -313,21 +348,49 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_bf16_kernel(const At
 #pragma unroll
         for (int w = 0; w < 4; ++w) pb[pp].w[w] = pack2(p[8 * pp + 2 * w], p[8 * pp + 2 * w + 1]);
 #pragma unroll
-      for (int pp = 0; pp < 2; ++pp) {
-        const int pgi = 2 * sb + pp;
+      for (int i = 0; i < 8; ++i) {
+        o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i].v, pb[i >> 2].v, o[i & 3], 0, 0, 0);
+        if (sb == 0) ring[i].u = vt[((2 + (i >> 2)) * kD + 32 * (i & 3)) * 2];   // pages 2, 3 of the tile
+      }
+      if (sb == 0) {
 #pragma unroll
-        for (int db = 0; db < 4; ++db) {
-          const int d = 32 * db + l32;
-          Frag va;
-          va.u = tiles[buf].v[(pgi * kD + d) * 2 + half];
-          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.v, pb[pp].v, o[db], 0, 0, 0);
+        for (int i = 0; i < 8; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
       }
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
-  for (int t = 0; t < n_tiles; t += 2) {
-    tile_step(t, std::integral_constant<int, 0>{});
-    if (t + 1 < n_tiles) tile_step(t + 1, std::integral_constant<int, 1>{});
+  // Two groups of waves (one wave of each per SIMD) run the same sequence one segment apart, so that the matrix
+  // segments of one fall on the vector segments of the other: group 0 stages the next tile BEFORE the tile's one
+  // barrier, group 1 AFTER it. Three LDS buffers, so that staging tile t+1 never touches what tile t-1's products
+  // still read.
+  const int grp = wave >> 2;
+  if (n_tiles > 0) {
+    pages_of(0, np0, np1, np2, np3);
+    load_tile(0, np0, np1, np2, np3);
+    stage_tile(0, 0);
+    pages_of(1, np0, np1, np2, np3);
+    if (n_tiles > 1) load_tile(1, np0, np1, np2, np3);
+    lds_barrier();
+  }
+  int bi = 0;
+  for (int t = 0; t < n_tiles; ++t) {
+    const int bn = bi + 1 == kNBuf ? 0 : bi + 1;
+    // page ids of tile t + 3: scalar loads, issued here so that the barrier's wait covers them (they share a counter
+    // with the LDS reads, and return out of order: one in flight would turn every LDS wait into a full drain)
+    if (grp) lds_barrier();
+    if (t + 1 < n_tiles) {
+      stage_tile(bn, (t + 1) * kTile);
+      if (t + 2 < n_tiles) {
+        pages_of(t + 2, np0, np1, np2, np3);
+        load_tile(t + 2, np0, np1, np2, np3);
+      }
+    }
+    if (!grp) lds_barrier();
+    tile_step(t, bi);
+    bi = bn;
   }
 
   // ---- normalise and store: lane (row l32, half) holds dims 32db + 8blk + 4half + e of its row ----
@@ -362,7 +425,15 @@ hipError_t launch_prefill_mfma_bf16(const AttnArgs& a, hipStream_t s) {
   if (e != hipSuccess) return e;
   const unsigned grid = (unsigned)a.B * a.Hkv * a.n_splits;
   if (a.timing_start) (void)hipEventRecord(reinterpret_cast<hipEvent_t>(a.timing_start), s);
-  hipLaunchKernelGGL(prefill_mfma_bf16_kernel, dim3(grid), dim3(kThreads), 0, s, a);
+  // three tile buffers are more LDS than a kernel gets by default: ask once per process (the attribute sticks)
+  static std::once_flag lds_once;
+  static hipError_t lds_status = hipSuccess;
+  std::call_once(lds_once, [] {
+    lds_status = hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_mfma_bf16_kernel),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kNBuf * sizeof(Tile)));
+  });
+  if (lds_status != hipSuccess) return lds_status;
+  hipLaunchKernelGGL(prefill_mfma_bf16_kernel, dim3(grid), dim3(kThreads), kNBuf * sizeof(Tile), s, a);
   e = hipGetLastError();
   if (a.timing_stop) (void)hipEventRecord(reinterpret_cast<hipEvent_t>(a.timing_stop), s);
   return e;
