@@ -6,7 +6,9 @@
  * Paper passages each call follows are cited per declaration (section / algorithm / figure only).
  *
  * Conventions that hold for every call:
- *   - returns a mepic_status (0 = ok, negative = error); nothing throws or aborts across the ABI;
+ *   - returns a mepic_status (0 = ok, negative = error); nothing throws or aborts across the ABI (a host
+ *     allocation that fails inside the pool or the planner comes back as MEPIC_ERR_NOMEM; a pool that reported it
+ *     from mepic_align_request or mepic_release_request is in an unspecified state and can only be destroyed);
  *   - the caller owns every buffer. "device" pointers are HIP device memory reachable from the
  *     current device; "host" pointers are ordinary host memory. The library never allocates or frees
  *     device memory; the pool owns only its own host metadata;
@@ -127,11 +129,14 @@ int mepic_align_request(mepic_pool* pool, const mepic_segment* segs, uint32_t n_
                         uint8_t* block_kind_out, uint32_t* block_valid_out, int32_t* block_pos_out,
                         uint64_t* request_handle_out, mepic_align_info* info_out);
 
-/* Drop a request: its private pages return to the free list, each chunk occurrence gives back one
- * reference; chunks that reach zero stay resident until evicted. MEPIC_ERR_INVALID for an unknown
- * handle. */
+/* Drop a request (§3.2.3, reference counts of the shared block pool): its private pages return to the free
+ * list, each chunk occurrence gives back one reference; chunks that reach zero stay resident, as candidates of
+ * the lazy eviction, until admission needs their pages. MEPIC_ERR_INVALID for an unknown handle. */
 int mepic_release_request(mepic_pool* pool, uint64_t request_handle);
 
+/* Page accounting (the HBM-usage metric of §4.1 and the comparison of §4.3 / §4.4 in pages): what the sharing
+ * pool holds now and at its peak, next to what a layout in which every request owns all of its blocks would
+ * hold. MEPIC_ERR_INVALID for null pointers. */
 int mepic_pool_get_stats(const mepic_pool* pool, mepic_pool_stats* out);
 
 /* Is the chunk resident, and with how many references? Returns MEPIC_OK and writes 0/1 to
@@ -184,7 +189,9 @@ typedef struct {
   const float* k_scales;            /* device [num_pages] fp32; required iff kv_dtype == F8E4M3:      */
   const float* v_scales;            /*   stored value = e4m3fn code * scale of its page; scales are
                                        magnitudes (amax / 448): finite and >= 0                       */
-  const int32_t* block_tables;      /* device [B][max_blocks] physical page ids in [0, num_pages)     */
+  const int32_t* block_tables;      /* device [B][max_blocks] physical page ids in [0, num_pages); an id
+                                       outside that range is forced into it on the device (no fault; the
+                                       result of that request is unspecified)                           */
   const int32_t* kv_lens;           /* device [B] valid KV slots per request (<= max_blocks * P)      */
   const int32_t* q_positions;       /* device [n_q_tokens] absolute position of each query token      */
   const int32_t* cu_q_lens;         /* device [B+1] prefix sums of query tokens per request; prefill
@@ -200,15 +207,19 @@ typedef struct {
   float rope_theta;
   float sm_scale;                   /* <= 0 means 1/sqrt(D)                                           */
   uint32_t flags;                   /* MEPIC_FLAG_*                                                   */
-  void* workspace;                  /* device scratch for split-K partials, 256-byte aligned          */
+  void* workspace;                  /* device scratch (split-K partials; rotary table of the matrix-core
+                                       prefill), 256-byte aligned                                       */
   size_t workspace_bytes;
   void* timing_start;               /* optional hipEvent_t pair (both or neither): recorded on the stream     */
   void* timing_stop;                /*   right before / after the call's main kernel, i.e. without the small  */
                                     /*   merge kernel that follows it in decode. A profiling aid; NULL = off.  */
 } mepic_attn_params;
 
-/* Bytes of workspace mepic_attn_decode / mepic_attn_prefill need for these shapes (only the shape,
- * dtype and max_* fields are read). */
+/* Bytes of workspace mepic_attn_decode / mepic_attn_prefill need. Read: the shape, dtype and max_* fields, the
+ * flags, and WHETHER block_positions / block_valid_mask are NULL (they and the flags select the kernel, and the
+ * kernels differ in what they need: split-K partials in decode, the per-position rotary table in the matrix-core
+ * prefill). Query with the same flags and the same NULL-ness of those two pointers as the call will have;
+ * a size queried otherwise can be too small, which the call reports as MEPIC_ERR_CAPACITY. */
 int mepic_attn_workspace_size(const mepic_attn_params* params, int is_prefill, size_t* bytes_out);
 
 /* Decode: one query token per request attends to all of the request's valid slots (§3.3.3). */
@@ -236,6 +247,16 @@ int mepic_attn_prefill(const mepic_attn_params* params, void* hip_stream);
 /* Name of the kernel variant the last attention call on this thread dispatched to (static string;
  * "" before any call). For tests and reports. */
 const char* mepic_last_kernel(void);
+
+/*
+ * Self-test of one building block, for the test suite (a guard against toolchain changes, not part of the method):
+ * the bf16 decode kernel rotates K (§3.3.3) with two-term dot-product instructions issued as a hand-written block
+ * whose hazard rules the compiler does not see. This call runs that block alone. words_device: device uint32
+ * [n][12] = four words (low element, high element) of rotary pairs as packed bf16, then for each of the four the
+ * constant words (cos, -sin) and (sin, cos) as packed bf16; out_device: device float [n][8] = the four rotated low
+ * elements, then the four rotated high elements, in fp32. Errors: MEPIC_ERR_INVALID, MEPIC_ERR_LAUNCH.
+ */
+int mepic_selftest_dot_rotation(const uint32_t* words_device, float* out_device, int32_t n, void* hip_stream);
 
 /* ------------------------------------------------------------------------------------------------
  * Commit to paged KV (§3.3.2): the K and V vectors just computed for new tokens (prompt tokens, the

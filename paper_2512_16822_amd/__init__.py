@@ -26,7 +26,7 @@ EXPORTS = ["mepic_strerror", "mepic_version", "mepic_pool_create", "mepic_pool_d
            "mepic_release_request", "mepic_pool_get_stats", "mepic_pool_lookup_chunk", "mepic_attn_workspace_size",
            "mepic_attn_decode", "mepic_attn_prefill", "mepic_last_kernel", "mepic_kv_commit",
            "mepic_decode_plan_capacity", "mepic_decode_plan_build", "mepic_attn_decode_batched_workspace_size",
-           "mepic_attn_decode_batched", "mepic_attn_decode_noalloc"]
+           "mepic_attn_decode_batched", "mepic_attn_decode_noalloc", "mepic_selftest_dot_rotation"]
 
 
 class MepicError(RuntimeError):
@@ -114,6 +114,7 @@ def load() -> ctypes.CDLL:
     lib.mepic_attn_decode.argtypes = [ctypes.POINTER(AttnParams), ctypes.c_void_p]
     lib.mepic_attn_prefill.argtypes = [ctypes.POINTER(AttnParams), ctypes.c_void_p]
     lib.mepic_attn_decode_noalloc.argtypes = [ctypes.POINTER(AttnParams), ctypes.c_void_p]
+    lib.mepic_selftest_dot_rotation.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p]
     lib.mepic_kv_commit.argtypes = [ctypes.POINTER(CommitParams), ctypes.c_void_p]
     lib.mepic_decode_plan_capacity.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                                ctypes.POINTER(ctypes.c_size_t)]
@@ -275,6 +276,13 @@ def attn_decode_noalloc(params: AttnParams, stream=None) -> None:
     rc = load().mepic_attn_decode_noalloc(ctypes.byref(params), _stream_handle(stream))
     if rc != OK:
         raise MepicError(rc, "mepic_attn_decode_noalloc")
+
+
+def selftest_dot_rotation(words, out, stream=None) -> None:
+    """mepic_selftest_dot_rotation: words uint32 [n, 12] (int32 tensor), out float32 [n, 8], both on the GPU."""
+    rc = load().mepic_selftest_dot_rotation(_p(words), _p(out), words.shape[0], _stream_handle(stream))
+    if rc != OK:
+        raise MepicError(rc, "mepic_selftest_dot_rotation")
 
 
 def attn_prefill(params: AttnParams, stream=None) -> None:

@@ -72,7 +72,7 @@ Plan make_plan(const mepic_attn_params* p, bool prefill) {
 
   const bool mfma_bf16 = p->q_dtype == MEPIC_BF16 && p->kv_dtype == MEPIC_BF16 && p->D == 128 && p->P == 16;
   const bool mfma_fp8 = p->q_dtype == MEPIC_BF16 && p->kv_dtype == MEPIC_F8E4M3 && p->D == 128 && p->P == 32;
-  if (!prefill && plain && G <= 16 && (mfma_bf16 || mfma_fp8)) {
+  if (!prefill && plain && G <= 16 && (mfma_bf16 || mfma_fp8) && p->B <= decode_mfma_max_requests()) {
     // Matrix-core decode: persistent waves cut each KV head's sequence of steps into equal chunks; here only
     // the bound on partials per request (sizes the workspace) and the minimum chunk are fixed.
     pl.kernel = mfma_fp8 ? K_DECODE_MFMA_F8 : K_DECODE_MFMA_BF16;
@@ -289,5 +289,12 @@ int mepic_attn_prefill(const mepic_attn_params* params, void* hip_stream) {
 }
 
 const char* mepic_last_kernel(void) { return mepic::g_last_kernel; }
+
+int mepic_selftest_dot_rotation(const uint32_t* words_device, float* out_device, int32_t n, void* hip_stream) {
+  if (n < 0 || (n && (!words_device || !out_device))) return MEPIC_ERR_INVALID;
+  if (n == 0) return MEPIC_OK;
+  const hipError_t e = mepic::launch_dot_rotate_selftest(words_device, out_device, n, reinterpret_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? MEPIC_OK : MEPIC_ERR_LAUNCH;
+}
 
 }  // extern "C"

@@ -75,6 +75,8 @@ hipError_t launch_prefill_mfma_bf16(const AttnArgs& a, hipStream_t s);  // n_spl
 int prefill_mfma_rows_per_workgroup();
 int prefill_mfma_table_positions(int max_kv_len);                    // positions its rotary table covers (16 bytes x 32 each)
 void decode_mfma_plan(int B, int Hkv, int max_kv_len, bool fp8, int* max_splits, int* min_chunk);
+hipError_t launch_dot_rotate_selftest(const uint32_t* words, float* out, int n, hipStream_t s);
+int decode_mfma_max_requests();                                       // B the plain walker's LDS has room for
 int decode_mfma_waves_per_head(int Hkv, bool fp8);                   // waves that share one KV head's steps
 hipError_t launch_decode_mfma_batched(const AttnArgs& a, int n_runs, hipStream_t s);  // plan-driven variant
 

@@ -118,6 +118,10 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
+// A page id as the kernels use it: forced into [0, num_pages) so that a corrupt block table reads a wrong page
+// instead of faulting (the result of that request is then unspecified, nothing else is affected).
+__device__ __forceinline__ int safe_page(int id, int num_pages) { return max(min(id, num_pages - 1), 0); }
+
 // 16- and 8-byte loads of page data, optionally with the non-temporal hint (the line is not kept in the caches):
 // right when every page is read by one request only, wrong when pages are shared between requests.
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
@@ -167,6 +171,32 @@ __device__ __forceinline__ float sum_over_kgroups(float x) {
   const uint32_t v = __float_as_uint(y);
   const auto b = __builtin_amdgcn_permlane32_swap(v, v, false, false);
   return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
+// Eight two-term dot products on packed bf16 words, fp32 results: l_i = e_i . ca_i, h_i = e_i . cb_i, where
+// e_i = (low element, high element) of a rotary pair and ca = (cos, -sin), cb = (sin, cos) as packed bf16.
+// One block of eight v_dot2_f32_bf16 closed by four wait states: another vector instruction may neither read the
+// result of a dot instruction for three wait states nor rewrite its register for four, and the compiler places those
+// only around its own builtin. Within the block no dot reads or rewrites another's result; the outputs are
+// early-clobber, so none shares a register with an input. Validated on ROCm 7.2 (AMD clang 22, gfx950); the
+// library's self-test entry point runs this block alone against fp32 arithmetic so that a toolchain that breaks the
+// rule shows up as a failed test and not as slightly wrong attention.
+__device__ __forceinline__ void dot_rotate_block(uint32_t e0, uint32_t e1, uint32_t e2, uint32_t e3, uint32_t ca0,
+                                                 uint32_t cb0, uint32_t ca1, uint32_t cb1, uint32_t ca2, uint32_t cb2,
+                                                 uint32_t ca3, uint32_t cb3, float& l0, float& l1, float& l2, float& l3,
+                                                 float& h0, float& h1, float& h2, float& h3) {
+  asm("v_dot2_f32_bf16 %0, %8, %12, 0\n\t"
+      "v_dot2_f32_bf16 %1, %9, %14, 0\n\t"
+      "v_dot2_f32_bf16 %2, %10, %16, 0\n\t"
+      "v_dot2_f32_bf16 %3, %11, %18, 0\n\t"
+      "v_dot2_f32_bf16 %4, %8, %13, 0\n\t"
+      "v_dot2_f32_bf16 %5, %9, %15, 0\n\t"
+      "v_dot2_f32_bf16 %6, %10, %17, 0\n\t"
+      "v_dot2_f32_bf16 %7, %11, %19, 0\n\t"
+      "s_nop 3"
+      : "=&v"(l0), "=&v"(l1), "=&v"(l2), "=&v"(l3), "=&v"(h0), "=&v"(h1), "=&v"(h2), "=&v"(h3)
+      : "v"(e0), "v"(e1), "v"(e2), "v"(e3), "v"(ca0), "v"(cb0), "v"(ca1), "v"(cb1), "v"(ca2), "v"(cb2), "v"(ca3),
+        "v"(cb3));
 }
 
 constexpr float kPScaleFp8 = 4.f;     // probabilities (< 2^slack = 64) are multiplied by this before the e4m3 split
@@ -370,28 +400,13 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8, kBatched)) void decode
           for (int w = 0; w < 4; w += 2) {  // pairs 8h + 2w .. 8h + 2w + 3
             // Bring the low and the high element of a pair into one word (v_perm_b32); each rotated element is then
             // one two-term dot product with a constant word, (cos, -sin) or (sin, cos), accumulated in fp32.
-            // Written as one block of eight v_dot2_f32_bf16 followed by four wait states, because another vector
-            // instruction may neither read the result of a dot instruction for three wait states nor rewrite its
-            // register for four, and the compiler places those only around its own builtin — which it lowers to the
-            // accumulating two-operand form plus a move that zeroes the accumulator (no gain). Within the block no
-            // dot reads or rewrites another's result. Early-clobber outputs: none may share a register with an input.
             const uint32_t la = kf[u][h].w[w], ha = kf[u][h + 2].w[w], lb = kf[u][h].w[w + 1], hb = kf[u][h + 2].w[w + 1];
             const uint32_t e0 = __builtin_amdgcn_perm(ha, la, 0x05040100u), e1 = __builtin_amdgcn_perm(ha, la, 0x07060302u);
             const uint32_t e2 = __builtin_amdgcn_perm(hb, lb, 0x05040100u), e3 = __builtin_amdgcn_perm(hb, lb, 0x07060302u);
             float l0, l1, l2, l3, h0, h1, h2, h3;
-            asm("v_dot2_f32_bf16 %0, %8, %12, 0\n\t"
-                "v_dot2_f32_bf16 %1, %9, %14, 0\n\t"
-                "v_dot2_f32_bf16 %2, %10, %16, 0\n\t"
-                "v_dot2_f32_bf16 %3, %11, %18, 0\n\t"
-                "v_dot2_f32_bf16 %4, %8, %13, 0\n\t"
-                "v_dot2_f32_bf16 %5, %9, %15, 0\n\t"
-                "v_dot2_f32_bf16 %6, %10, %17, 0\n\t"
-                "v_dot2_f32_bf16 %7, %11, %19, 0\n\t"
-                "s_nop 3"
-                : "=&v"(l0), "=&v"(l1), "=&v"(l2), "=&v"(l3), "=&v"(h0), "=&v"(h1), "=&v"(h2), "=&v"(h3)
-                : "v"(e0), "v"(e1), "v"(e2), "v"(e3), "v"(__float_as_uint(r[w].x)), "v"(__float_as_uint(r[w].y)),
-                  "v"(__float_as_uint(r[w].z)), "v"(__float_as_uint(r[w].w)), "v"(__float_as_uint(r[w + 1].x)),
-                  "v"(__float_as_uint(r[w + 1].y)), "v"(__float_as_uint(r[w + 1].z)), "v"(__float_as_uint(r[w + 1].w)));
+            dot_rotate_block(e0, e1, e2, e3, __float_as_uint(r[w].x), __float_as_uint(r[w].y), __float_as_uint(r[w].z),
+                             __float_as_uint(r[w].w), __float_as_uint(r[w + 1].x), __float_as_uint(r[w + 1].y),
+                             __float_as_uint(r[w + 1].z), __float_as_uint(r[w + 1].w), l0, l1, l2, l3, h0, h1, h2, h3);
             klo.w[w] = pack_bf16x2(l0, l1);
             klo.w[w + 1] = pack_bf16x2(l2, l3);
             khi.w[w] = pack_bf16x2(h0, h1);
@@ -569,12 +584,12 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8, kBatched)) void decode
       const int req0 = uni(m.req0);
       if (uni(m.w0) & kPlanGather) {  // the piece's steps and their pages from the gather section (64 at most)
         const int32_t* g = gather_list + (size_t)(uni(m.step0) + (m.pos - m.c0) + min(lane, m.n_st - 1)) * kPlanGatherWords;
-        m.gs = g[0]; m.bt0 = g[1]; m.bt1 = g[2];
+        m.gs = g[0]; m.bt0 = safe_page(g[1], a.num_pages); m.bt1 = safe_page(g[2], a.num_pages);
       } else {
         const int j0 = kBps * (uni(m.step0) + (m.pos - m.c0)), jl = uni(m.jlast);
         const size_t row = (size_t)req0 * a.max_blocks;
-        m.bt0 = a.block_tables[row + min(j0 + lane, jl)];
-        m.bt1 = a.block_tables[row + min(j0 + 64 + lane, jl)];
+        m.bt0 = safe_page(a.block_tables[row + min(j0 + lane, jl)], a.num_pages);
+        m.bt1 = safe_page(a.block_tables[row + min(j0 + 64 + lane, jl)], a.num_pages);
         m.gs = 0;
       }
       m.L = a.kv_lens[req0];
@@ -618,7 +633,7 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8, kBatched)) void decode
       const int L = uni(cur.L), j0 = kBps * step_first;
       const bool ragged_end = (step_first + n_st) * 32 > L;  // only a run of one request can reach past kv_len
       const size_t bt_row = (size_t)req0 * a.max_blocks;
-      auto bt_load = [&](int win) { return a.block_tables[bt_row + min(j0 + 64 * win + lane, jl)]; };
+      auto bt_load = [&](int win) { return safe_page(a.block_tables[bt_row + min(j0 + 64 * win + lane, jl)], a.num_pages); };
       int bt_win = 0, bt_cur = cur.bt0, bt_nxt = cur.bt1;
       auto page = [&](int st, int k) __attribute__((always_inline)) {  // page k of step st; called with non-decreasing st
         if (gather) return __builtin_amdgcn_readlane(k ? bt_nxt : bt_cur, st);
@@ -753,7 +768,7 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8, kBatched)) void decode
     // request's last block), bt_nxt the 64 after those; a step reads its ids with v_readlane. Vector loads on
     // purpose: scalar loads share a counter with the LDS reads, so every wait for a rotation constant would
     // also wait for them. The next window is fetched a whole window ahead.
-    auto bt_load = [&](int win) { return a.block_tables[bt_row + min(j0 + 64 * win + lane, jend - 1)]; };
+    auto bt_load = [&](int win) { return safe_page(a.block_tables[bt_row + min(j0 + 64 * win + lane, jend - 1)], a.num_pages); };
     int bt_win = 0, bt_cur = bt_load(0), bt_nxt = bt_load(1);
     auto page = [&](int st, int k) {  // page k of step st; called with non-decreasing st
       const int rel = kBps * st + k;
@@ -924,15 +939,26 @@ __global__ __launch_bounds__(128) void combine_batched_kernel(const AttnArgs a) 
             reinterpret_cast<uint16_t*>(a.out) + (size_t)row * kD);
 }
 
+// Self-test of dot_rotate_block: words[i] = {e0..e3, ca0, cb0, ca1, cb1, ca2, cb2, ca3, cb3}; out[i] = {l0..l3, h0..h3}.
+__global__ __launch_bounds__(256) void dot_rotate_selftest_kernel(const uint32_t* words, float* out, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const uint32_t* w = words + (size_t)i * 12;
+  float r[8];
+  dot_rotate_block(w[0], w[1], w[2], w[3], w[4], w[5], w[6], w[7], w[8], w[9], w[10], w[11], r[0], r[1], r[2], r[3], r[4],
+                   r[5], r[6], r[7]);
+#pragma unroll
+  for (int k = 0; k < 8; ++k) out[(size_t)i * 8 + k] = r[k];
+}
+
 int compute_units() {
-  static int cus = 0;
-  if (!cus) {
+  static const int cus = [] {  // initialised once, thread-safely (function-local static)
     int dev = 0, n = 0;
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
       n = 256;
-    cus = n;
-  }
+    return n;
+  }();
   return cus;
 }
 
@@ -963,16 +989,16 @@ hipError_t launch_decode_mfma_batched(const AttnArgs& a, int n_runs, hipStream_t
   const bool fp8 = a.kv_dtype == MEPIC_F8E4M3;
   const int n_wg = max(wg_per_cu(fp8, true) * compute_units() / a.Hkv, 1) * a.Hkv;
   const size_t lds = (size_t)(n_runs + 1) * sizeof(int);
-  static bool lds_limit_raised = false;  // static + dynamic LDS may pass 64 KB (the caller bounds n_runs): ask for it
-  if (!lds_limit_raised) {
+  // static + dynamic LDS may pass 64 KB (the caller bounds n_runs): ask for it, once per process
+  static const hipError_t lds_limit_status = [] {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_mfma_kernel<true, true>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 48 * 1024);
     if (e == hipSuccess)
       e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_mfma_kernel<false, true>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, 48 * 1024);
-    if (e != hipSuccess) return e;
-    lds_limit_raised = true;
-  }
+    return e;
+  }();
+  if (lds_limit_status != hipSuccess) return lds_limit_status;
   if (a.timing_start) (void)hipEventRecord(reinterpret_cast<hipEvent_t>(a.timing_start), s);
   if (fp8)
     hipLaunchKernelGGL((decode_mfma_kernel<true, true>), dim3(n_wg), dim3(64 * kWaves), lds, s, a);
@@ -982,6 +1008,15 @@ hipError_t launch_decode_mfma_batched(const AttnArgs& a, int n_runs, hipStream_t
   if (a.timing_stop) (void)hipEventRecord(reinterpret_cast<hipEvent_t>(a.timing_stop), s);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(combine_batched_kernel, dim3(a.n_q * a.Hq), dim3(kD), 0, s, a);
+  return hipGetLastError();
+}
+
+// Requests one plain decode call can take: the per-request step counts (B + 1 ints of dynamic LDS) must fit beside the
+// kernel's static tables in the 64 KB a workgroup gets without asking for more.
+int decode_mfma_max_requests() { return (64 * 1024 - 44 * 1024) / (int)sizeof(int) - 1; }
+
+hipError_t launch_dot_rotate_selftest(const uint32_t* words, float* out, int n, hipStream_t s) {
+  hipLaunchKernelGGL(dot_rotate_selftest_kernel, dim3((n + 255) / 256), dim3(256), 0, s, words, out, n);
   return hipGetLastError();
 }
 

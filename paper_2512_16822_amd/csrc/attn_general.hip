@@ -131,7 +131,7 @@ __global__ __launch_bounds__(kThreads) void attn_general_kernel(const AttnArgs a
     int pos_k = n, page = 0;
     const int j = n / P, sl = n % P;
     if (take) {
-      page = a.block_tables[bt_row + j];
+      page = max(min(a.block_tables[bt_row + j], a.num_pages - 1), 0);  // a corrupt id reads a wrong page, never faults
       if (a.block_valid_mask) take = (a.block_valid_mask[bt_row + j] >> sl) & 1u;
       if (a.block_positions) pos_k = a.block_positions[bt_row + j] + sl;
       if (a.causal && pos_k > pos_q) take = false;
@@ -218,7 +218,7 @@ __global__ __launch_bounds__(kThreads) void attn_general_kernel(const AttnArgs a
     const int tile_blocks = (min(n0 + kThreads, n_end) - n0 + P - 1) / P;
     for (int jb = part; jb < tile_blocks; jb += parts) {
       const int nb0 = n0 + jb * P;  // first slot of the block; n0 is a multiple of P
-      const int pg = a.block_tables[bt_row + nb0 / P];
+      const int pg = max(min(a.block_tables[bt_row + nb0 / P], a.num_pages - 1), 0);
       const float vsc = KV == MEPIC_F8E4M3 ? a.v_scales[pg] : 1.f;
       const size_t row = (((size_t)pg * a.Hkv + hk) * D + d_own) * (size_t)P;  // in elements
       for (int c = 0; c < P / X; ++c) {

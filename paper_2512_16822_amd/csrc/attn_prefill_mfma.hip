@@ -238,7 +238,10 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_bf16_kernel(const At
   // request's last block), bt_nxt the 64 after those; a tile reads its four ids with v_readlane. Vector loads on
   // purpose: scalar loads share a counter with the LDS reads and return out of order, so one in flight would turn
   // every wait for an LDS operand into a full drain.
-  auto bt_load = [&](int win) { return a.block_tables[bt_row + min(64 * win + lane, max(n_blocks - 1, 0))]; };
+  // (ids forced into [0, num_pages): a corrupt table reads a wrong page instead of faulting)
+  auto bt_load = [&](int win) {
+    return max(min(a.block_tables[bt_row + min(64 * win + lane, max(n_blocks - 1, 0))], a.num_pages - 1), 0);
+  };
   int bt_win = 0, bt_cur = 0, bt_nxt = 0;
   if (n_tiles > 0) {   // (a request without visible slots has nothing to read, possibly not even a block table)
     bt_cur = bt_load(0);
