@@ -340,6 +340,21 @@ int mepic_decode_plan_build(const int32_t* block_tables_host, const int32_t* kv_
                             int32_t max_blocks, int32_t P, int32_t Hq, int32_t Hkv, int32_t kv_dtype,
                             int32_t* plan_out_host, size_t capacity_int32, mepic_decode_plan_info* info_out);
 
+/*
+ * The same planner, planning ahead so that one plan serves several decode steps: every request is planned as if
+ * it were `horizon_tokens` longer. The steps it will grow into are in the plan as steps of its own, masked in the
+ * kernel against the kv_lens of the call, so the plan stays valid for any call with
+ *     kv_lens_host[b] <= kv_lens[b] <= kv_lens_host[b] + horizon_tokens   for every request b
+ * and the block tables it was built from. Those tables must therefore already hold the pages of the slots ahead
+ * (align the request with extra_tail_tokens >= horizon_tokens), and max_blocks * P must cover them (lengths are
+ * planned up to that bound only). In a decode loop this is one plan per horizon_tokens decode steps, shared by all
+ * layers; horizon_tokens = 0 is mepic_decode_plan_build. Errors as there; horizon_tokens < 0 is MEPIC_ERR_INVALID.
+ */
+int mepic_decode_plan_build_ahead(const int32_t* block_tables_host, const int32_t* kv_lens_host, int32_t B,
+                                  int32_t max_blocks, int32_t P, int32_t Hq, int32_t Hkv, int32_t kv_dtype,
+                                  int32_t horizon_tokens, int32_t* plan_out_host, size_t capacity_int32,
+                                  mepic_decode_plan_info* info_out);
+
 /* Workspace bytes mepic_attn_decode_batched needs for this plan. */
 int mepic_attn_decode_batched_workspace_size(const mepic_attn_params* params, const mepic_decode_plan_info* info,
                                              size_t* bytes_out);

@@ -26,7 +26,8 @@ EXPORTS = ["mepic_strerror", "mepic_version", "mepic_pool_create", "mepic_pool_d
            "mepic_release_request", "mepic_pool_get_stats", "mepic_pool_lookup_chunk", "mepic_attn_workspace_size",
            "mepic_attn_decode", "mepic_attn_prefill", "mepic_last_kernel", "mepic_kv_commit",
            "mepic_decode_plan_capacity", "mepic_decode_plan_build", "mepic_attn_decode_batched_workspace_size",
-           "mepic_attn_decode_batched", "mepic_attn_decode_noalloc", "mepic_selftest_dot_rotation"]
+           "mepic_attn_decode_batched", "mepic_attn_decode_noalloc", "mepic_selftest_dot_rotation",
+           "mepic_decode_plan_build_ahead"]
 
 
 class MepicError(RuntimeError):
@@ -119,6 +120,8 @@ def load() -> ctypes.CDLL:
     lib.mepic_decode_plan_capacity.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                                ctypes.POINTER(ctypes.c_size_t)]
     lib.mepic_decode_plan_build.argtypes = [ctypes.c_void_p, ctypes.c_void_p] + [ctypes.c_int32] * 6 + [
+        ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(DecodePlanInfo)]
+    lib.mepic_decode_plan_build_ahead.argtypes = [ctypes.c_void_p, ctypes.c_void_p] + [ctypes.c_int32] * 7 + [
         ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(DecodePlanInfo)]
     lib.mepic_attn_decode_batched_workspace_size.argtypes = [ctypes.POINTER(AttnParams), ctypes.POINTER(DecodePlanInfo),
                                                              ctypes.POINTER(ctypes.c_size_t)]
@@ -292,8 +295,9 @@ def attn_prefill(params: AttnParams, stream=None) -> None:
         raise MepicError(rc, "mepic_attn_prefill")
 
 
-def decode_plan_build(block_tables, kv_lens, P: int, Hq: int, Hkv: int, kv_dtype: int):
-    """mepic_decode_plan_build on host arrays (numpy int32). Returns (plan words as a numpy int32 array, info)."""
+def decode_plan_build(block_tables, kv_lens, P: int, Hq: int, Hkv: int, kv_dtype: int, horizon_tokens: int = 0):
+    """mepic_decode_plan_build (horizon_tokens = 0) or mepic_decode_plan_build_ahead on host arrays (numpy int32).
+    Returns (plan words as a numpy int32 array, info)."""
     import numpy as np
     bt = np.ascontiguousarray(block_tables, dtype=np.int32)
     kl = np.ascontiguousarray(kv_lens, dtype=np.int32)
@@ -304,8 +308,12 @@ def decode_plan_build(block_tables, kv_lens, P: int, Hq: int, Hkv: int, kv_dtype
         raise MepicError(rc, "mepic_decode_plan_capacity")
     plan = np.empty(max(int(cap.value), 1), dtype=np.int32)  # worst case; the library writes the words it uses
     info = DecodePlanInfo()
-    rc = load().mepic_decode_plan_build(bt.ctypes.data, kl.ctypes.data, B, max_blocks, P, Hq, Hkv, kv_dtype,
-                                        plan.ctypes.data, plan.size, ctypes.byref(info))
+    if horizon_tokens:
+        rc = load().mepic_decode_plan_build_ahead(bt.ctypes.data, kl.ctypes.data, B, max_blocks, P, Hq, Hkv, kv_dtype,
+                                                  horizon_tokens, plan.ctypes.data, plan.size, ctypes.byref(info))
+    else:
+        rc = load().mepic_decode_plan_build(bt.ctypes.data, kl.ctypes.data, B, max_blocks, P, Hq, Hkv, kv_dtype,
+                                            plan.ctypes.data, plan.size, ctypes.byref(info))
     if rc != OK:
         raise MepicError(rc, "mepic_decode_plan_build")
     return plan[: info.n_int32].copy(), info

@@ -451,6 +451,9 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8, kBatched)) void decode
       sc[1] *= ksc;
     }
     // lane (head n16, kg) now holds the scores of slots n0 + 8kg + 4u + e
+    // (a step wholly past kv_len, which a plan built ahead can hold, may read a page nobody has written yet: its V scale
+    // must not reach the arithmetic; its scores and V bytes are masked below like any slot past kv_len)
+    if (kFp8 && ragged && n0 >= L) vsc = v_ref;
     if (ragged) {
 #pragma unroll
       for (int u = 0; u < 2; ++u)

@@ -54,11 +54,19 @@ int mepic_decode_plan_capacity(int32_t B, int32_t max_blocks, int32_t P, size_t*
 int mepic_decode_plan_build(const int32_t* block_tables, const int32_t* kv_lens, int32_t B, int32_t max_blocks,
                             int32_t P, int32_t Hq, int32_t Hkv, int32_t kv_dtype, int32_t* plan_out,
                             size_t capacity_int32, mepic_decode_plan_info* info_out) {
+  return mepic_decode_plan_build_ahead(block_tables, kv_lens, B, max_blocks, P, Hq, Hkv, kv_dtype, 0, plan_out,
+                                       capacity_int32, info_out);
+}
+
+int mepic_decode_plan_build_ahead(const int32_t* block_tables, const int32_t* kv_lens, int32_t B, int32_t max_blocks,
+                                  int32_t P, int32_t Hq, int32_t Hkv, int32_t kv_dtype, int32_t horizon_tokens,
+                                  int32_t* plan_out, size_t capacity_int32, mepic_decode_plan_info* info_out) {
   try {
     using namespace mepic;
     if (!block_tables || !kv_lens || !plan_out || !info_out || B < 0 || max_blocks < 0 || Hq <= 0 || Hkv <= 0 ||
-        Hq % Hkv)
+        Hq % Hkv || horizon_tokens < 0)
       return MEPIC_ERR_INVALID;
+    const int horizon = horizon_tokens;
     const bool fp8 = kv_dtype == MEPIC_F8E4M3;
     if (!((kv_dtype == MEPIC_BF16 && P == 16) || (fp8 && P == 32))) return MEPIC_ERR_UNSUPPORTED;
     const int G = Hq / Hkv;
@@ -66,13 +74,18 @@ int mepic_decode_plan_build(const int32_t* block_tables, const int32_t* kv_lens,
     const int bps = 32 / P, r_cap = kPlanMaxR / G;
   
     // steps per request; where each request's steps start in one flat numbering
-    std::vector<int> nst(B), first(B + 1, 0);
+    // (planned for growth: the steps a request reaches within `horizon` more tokens are in the plan already, as steps
+    // of its own whose slots the kernel masks against the kv_len of the call)
+    std::vector<int> nst(B), first(B + 1, 0), lp(B);
     for (int b = 0; b < B; ++b) {
       const int L = kv_lens[b];
       if (L < 0 || (long)L > (long)max_blocks * P) return MEPIC_ERR_INVALID;
-      nst[b] = ((L + P - 1) / P + bps - 1) / bps;
+      lp[b] = (int)std::min<long>((long)L + horizon, (long)max_blocks * P);
+      nst[b] = ((lp[b] + P - 1) / P + bps - 1) / bps;
       first[b + 1] = first[b] + nst[b];
     }
+    // a step that is not wholly below the kv_len the plan is built from: the ragged last step and what lies ahead
+    auto is_tail = [&](int b, int st) { return (st + 1) * 32 > kv_lens[b]; };
     const int total = first[B];
   
     // group id of every step: steps wholly below kv_len whose pages coincide are grouped, at most r_cap requests
@@ -149,9 +162,14 @@ int mepic_decode_plan_build(const int32_t* block_tables, const int32_t* kv_lens,
         const StepRef* m0 = gm.data() + goff[g0];
         Run r{1, std::vector<StepRef>(m0, m0 + n0), {}};
         for (int k = 0; k < n0; ++k) done[first[m0[k].b] + m0[k].s] = 1;
-        for (;;) {
+        // With a horizon, every tail step is a run of its own (and so ends up in a gather run, the only kind whose
+        // steps are each masked against the call's kv_len); without one, a request's single ragged step may close a
+        // longer run, which masks its last step.
+        const bool tail_alone = horizon > 0 && is_tail(b, s);
+        for (; !tail_alone;) {
           const StepRef lead{m0[0].b, m0[0].s + r.n};
           if (lead.s >= nst[lead.b] || done[first[lead.b] + lead.s]) break;
+          if (horizon > 0 && is_tail(lead.b, lead.s)) break;
           const int g = gid[first[lead.b] + lead.s];
           const StepRef* m = gm.data() + goff[g];
           bool same = group_size(g) == n0;
@@ -260,7 +278,7 @@ int mepic_decode_plan_build(const int32_t* block_tables, const int32_t* kv_lens,
         cum[q] = pos;
         int32_t* w = rw + (size_t)q * kPlanRunWords;
         w[0] = (int32_t)r.at.size() | (q > i ? kPlanContinues : 0) | (r.steps.empty() ? 0 : kPlanGather);
-        w[kPlanRunWords - 1] = std::max((kv_lens[r.at[0].b] + P - 1) / P - 1, 0);  // clamp for the page-id loads
+        w[kPlanRunWords - 1] = std::max((lp[r.at[0].b] + P - 1) / P - 1, 0);  // clamp for the page-id loads
         for (size_t k = 0; k < r.at.size(); ++k) {
           w[1 + k] = r.at[k].b;
           w[1 + kPlanMaxR + k] = r.steps.empty() ? r.at[k].s : n_listed;
@@ -272,7 +290,7 @@ int mepic_decode_plan_build(const int32_t* block_tables, const int32_t* kv_lens,
           int32_t* g = gather + (size_t)n_listed++ * kPlanGatherWords;
           // the second block of a request's last step may lie past its blocks: the kernel masks those slots, the
           // page it reads them from only has to exist
-          const bool second = bps == 2 && st * bps + 1 < (kv_lens[r.at[0].b] + P - 1) / P;
+          const bool second = bps == 2 && st * bps + 1 < (lp[r.at[0].b] + P - 1) / P;
           g[0] = st; g[1] = pages[0]; g[2] = second ? pages[1] : pages[0];
         }
         pos += r.n;

@@ -89,6 +89,48 @@ def test_random_structures(mepic, oracle_attn, seed):
     check_batched(mepic, oracle_attn, case, rows=rows)
 
 
+@pytest.mark.parametrize("kv_dtype,P,G", [("bf16", 16, 4), ("f8e4m3", 32, 7), ("bf16", 16, 1)])
+def test_plan_built_ahead_serves_later_decode_steps(mepic, oracle_attn, kv_dtype, P, G):
+    """One plan built with a horizon of 40 tokens, then decode calls at kv_len + 0, 1, 17, 31, 32, 40 with the
+    device-side kv_lens and query positions of each step: every call against the oracle. The pages of the slots
+    ahead exist (the requests were aligned with that many tail tokens); what lies past the kv_len of a call is
+    poisoned with NaN for that call."""
+    H = 40
+    st = W.decode_structure(f"ahead_{kv_dtype}", 73 + G, B=10, Hq=2 * G, Hkv=2, D=128, P=P, theta=5e5, q_dtype="bf16",
+                            kv_dtype=kv_dtype, prefix=40, n_chunks=(1, 5), chunk_tokens=300, pool=3, question=45)
+    st.extra_tail = 1 + H                                       # the decode token and the H after it
+    aligned, _ = align_with_oracle(st)
+    full = W.assemble(st, aligned, poison=False)                # values for every slot up to the horizon
+    L0 = full.kv_lens - H
+    fmt = mepic.F8E4M3 if kv_dtype == "f8e4m3" else mepic.BF16
+    plan, info = mepic.decode_plan_build(full.block_tables, L0, P, st.Hq, st.Hkv, fmt, horizon_tokens=H)
+    for k in (0, 1, 17, 31, 32, 40):
+        case = W.Case(st, full.block_tables, full.n_blocks, (L0 + k).astype(np.int32), (L0 + k - 1).astype(np.int32),
+                      None, W.gen_pages(st.seed, full.pages.num_pages, st.Hkv, P, st.D, kv_dtype), full.q)
+        W.poison_tail(case.pages, case.block_tables, case.kv_lens)
+        for b in range(st.B):                                   # whole blocks past kv_len as well
+            for j in range(-(-int(case.kv_lens[b]) // P), int(case.n_blocks[b])):
+                page = int(case.block_tables[b, j])
+                if kv_dtype == "f8e4m3":
+                    case.pages.k.view(torch.uint8)[page] = 0x7F
+                    case.pages.v.view(torch.uint8)[page] = 0x7F
+                    case.pages.k_scales[page] = float("nan")
+                    case.pages.v_scales[page] = float("nan")
+                else:
+                    case.pages.k[page] = float("nan")
+                    case.pages.v[page] = float("nan")
+        dc = DeviceCase(mepic, case)
+        dc.plan_info, dc.plan = info, torch.from_numpy(plan).to(dc.q.device)
+        nbytes = mepic.attn_decode_batched_workspace_size(dc.params, info)
+        dc.ws = torch.empty(max(nbytes, dc.ws.numel()), dtype=torch.uint8, device=dc.q.device)
+        dc.params.workspace, dc.params.workspace_bytes = dc.ws.data_ptr(), dc.ws.numel()
+        got = dc.run_batched()
+        want = oracle_out(oracle_attn, case)
+        assert np.isfinite(got).all(), k
+        err = np.abs(got - want).max()
+        assert err <= TOL, (k, err)
+
+
 @pytest.mark.parametrize("cfg,n_rows", [(2, 2048), (4, 256), (5, 512)])
 def test_full_size_configs_sampled(mepic, oracle_attn, cfg, n_rows):
     st = W.config(cfg)

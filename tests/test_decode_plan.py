@@ -28,8 +28,9 @@ def parse(plan, info):
     return cum, runs, n_part, gather.reshape(n_gather, GATHER_WORDS), cuts
 
 
-def check_plan(M, bt, kv_lens, P, Hq, Hkv, kv_dtype):
-    plan, info = M.decode_plan_build(bt, kv_lens, P, Hq, Hkv, kv_dtype)
+def check_plan(M, bt, kv_lens, P, Hq, Hkv, kv_dtype, horizon=0):
+    plan, info = M.decode_plan_build(bt, kv_lens, P, Hq, Hkv, kv_dtype, horizon_tokens=horizon)
+    planned = [min(int(L) + horizon, bt.shape[1] * P) for L in kv_lens]      # lengths the plan reaches
     cum, runs, n_part, gather, cuts = parse(plan, info)
     listed = 0
     # the waves' ranges tile the sequence of steps; wave_of(p) = the wave whose range holds position p
@@ -39,7 +40,7 @@ def check_plan(M, bt, kv_lens, P, Hq, Hkv, kv_dtype):
     assert int(np.diff(cuts).max(initial=0)) <= 2 * -(-info.total_steps // info.n_waves) + 2
     bps, G = 32 // P, Hq // Hkv
     B = bt.shape[0]
-    nst = [(-(-int(L) // P) + bps - 1) // bps for L in kv_lens]
+    nst = [(-(-int(L) // P) + bps - 1) // bps for L in planned]
     assert info.steps_unbatched == sum(nst) and info.r_cap == 16 // G
     seen = [np.zeros(n, dtype=np.int32) for n in nst]
     used = [0] * B
@@ -66,7 +67,7 @@ def check_plan(M, bt, kv_lens, P, Hq, Hkv, kv_dtype):
         for k in range(R):
             assert slot[k] == chain_base[k] - chain_head_wave       # the kernel adds its wave index
         if is_gather:                                       # one request; listed steps, ascending, with their pages
-            b, L = int(req[0]), int(kv_lens[int(req[0])])
+            b, L = int(req[0]), planned[int(req[0])]
             assert R == 1 and n <= GATHER_MAX and step0[0] == listed
             entries = gather[listed:listed + n]
             listed += n
@@ -80,6 +81,8 @@ def check_plan(M, bt, kv_lens, P, Hq, Hkv, kv_dtype):
             continue
         if R == 1:                                          # short one-request runs were gathered
             assert n >= GATHER_BELOW
+        if horizon:                                         # planned ahead: only gather runs hold steps that reach past kv_len
+            assert all((int(step0[k]) + n) * 32 <= int(kv_lens[int(req[k])]) for k in range(R))
         for k in range(R):
             b, s0 = int(req[k]), int(step0[k])
             seen[b][s0:s0 + n] += 1
@@ -104,6 +107,25 @@ def test_plan_of_baseline_decode_configs(mepic, cfg):
                       mepic.F8E4M3 if st.kv_dtype == "f8e4m3" else mepic.BF16)
     ratio = info.steps_unbatched / info.total_steps
     assert ratio > (2.5 if cfg == 2 else 1.6), ratio          # shared chunk pages are walked once per group
+
+
+@pytest.mark.parametrize("horizon", [1, 32, 100])
+def test_plan_built_ahead(mepic, horizon):
+    """Planned for growth: the steps a request reaches within `horizon` tokens are covered, each exactly once, and
+    sit in gather runs (whose steps are masked one by one against the kv_len of the call)."""
+    st = W.decode_structure("ahead", 71, B=9, Hq=8, Hkv=2, D=128, P=16, theta=5e5, q_dtype="bf16", kv_dtype="bf16",
+                            prefix=40, n_chunks=(1, 5), chunk_tokens=300, pool=3, question=45)
+    aligned, _ = align_with_oracle(st)
+    case = W.assemble(st, aligned, poison=False)
+    bt = np.concatenate([case.block_tables, np.full((st.B, 8), 7, dtype=np.int32)], axis=1)   # room to grow: 128 slots
+    info0 = check_plan(mepic, bt, case.kv_lens, st.P, st.Hq, st.Hkv, mepic.BF16)
+    info = check_plan(mepic, bt, case.kv_lens, st.P, st.Hq, st.Hkv, mepic.BF16, horizon=horizon)
+    extra = sum(-(-(int(L) + horizon) // 32) - -(-int(L) // 32) for L in case.kv_lens)
+    assert info.steps_unbatched == info0.steps_unbatched + extra
+    # the table bounds the plan: no room, no steps ahead
+    info = check_plan(mepic, case.block_tables, case.kv_lens, st.P, st.Hq, st.Hkv, mepic.BF16, horizon=1000)
+    with pytest.raises(mepic.MepicError):
+        mepic.decode_plan_build(bt, case.kv_lens, st.P, st.Hq, st.Hkv, mepic.BF16, horizon_tokens=-1)
 
 
 def test_plan_edge_cases(mepic):
