@@ -1,17 +1,21 @@
 #!/usr/bin/env python3
 """Benchmark of the fused-RoPE paged-attention hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--layout both|shared|duplicated]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--only NAME[,NAME..]] [--no-cpu-baseline]
 
-A step is one attention call of the library over the whole batch of the workload (gather through the
-block tables, rotary embedding of K and Q on chip, online softmax, PV, split-K combine), with every
-input already resident in HBM. Block tables come from the library's own aligner before the timed
-region (the scheduling path runs once per request, not once per decode step); its cost is reported
-separately. The default workload is the Llama-3-8B-shaped decode configuration of the benchmark spec.
+With no flags it measures every workload of the benchmark spec that fits a roofline (configs 2, 3, 4, 5), the commit step
+(prompt shape in bf16 and bf16 -> e4m3, decode-step shape) and the matrix-instruction-only calibration kernel, and
+prints ONE JSON line. A step is one call of the library over the whole batch of the workload (gather through the
+block tables, rotary embedding of K and Q on chip, online softmax, PV, split-K combine), every input already
+resident in HBM. Block tables come from the library's own aligner before the timed region (the scheduling path runs
+once per request, not once per decode step); its cost is reported separately.
 
-Prints ONE JSON line. `value` is logical KV bytes per second on the page-sharing (MEPIC) layout;
-`roofline` is measured on the same logical workload laid out with one page per logical block, where
-every byte has to come from HBM (shared pages can be served from the caches).
+The top level of the line (`value`, `ms_per_step`, `config`, `roofline`, `cpu_baseline`) describes ONE run: the
+Llama-3-8B-shaped decode workload laid out with one page per logical block, so that every byte has to come from HBM,
+with the caller's read-once hint — a rate that can be held against the 8 TB/s peak. What the page-sharing layout
+delivers (pages served from L2 / Infinity Cache: a cache rate, not an HBM rate) is under `layouts`, the other
+workloads under `configs`. `--only` restricts the run to some records (names: cfg2 cfg3 cfg4 cfg5 commit_bf16
+commit_fp8 commit_decode mfma_probe), e.g. for a profiler; the top level then describes the first of them.
 """
 from __future__ import annotations
 
@@ -23,20 +27,21 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+N_LAYERS = 32            # layers that share one decode plan (block tables are per request, not per layer)
+PLAN_HORIZON = 32        # decode steps one plan built ahead serves
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# command (counter readings in KiB, each scaled by what the same counter reads for a 1 GiB device copy:
-# FETCH_SIZE x2.000, WRITE_SIZE x1.000). Summaries with the commands are under profiles/.
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command
+# (counter readings in KiB, each scaled by what the same counter reads for a 1 GiB device copy: FETCH_SIZE x2.000,
+# WRITE_SIZE x1.000). Summaries with the commands are under profiles/.
 MEASURED_TRAFFIC = {
-    ("cfg2_llama3_8b_decode_bf16", "duplicated", "decode_mfma_bf16"): int((583510.4 * 2.0 + 5221.6) * 1024),
-    ("cfg4_long_decode_bf16", "duplicated", "decode_mfma_bf16"): int((1112407.2 * 2.0 + 4236.3) * 1024),
-    ("cfg5_mixed_decode_fp8", "duplicated", "decode_mfma_fp8"): int((1119965.7 * 2.0 + 9261.2) * 1024),
-    ("cfg3_question_prefill_bf16", "shared", "prefill_mfma_bf16"): int((320040.3 * 2.0 + 32768.0) * 1024),
+    ("cfg2", "decode_mfma_bf16"): int((583510.4 * 2.0 + 5221.6) * 1024),
+    ("cfg4", "decode_mfma_bf16"): int((1112407.2 * 2.0 + 4236.3) * 1024),
+    ("cfg5", "decode_mfma_fp8"): int((1119965.7 * 2.0 + 9261.2) * 1024),
 }
+ALL = ["cfg2", "cfg3", "cfg4", "cfg5", "commit_bf16", "commit_fp8", "commit_decode", "mfma_probe"]
 
 
 def algorithmic_bytes(case) -> int:
@@ -65,13 +70,12 @@ def visible_pairs(case) -> int:
 
 
 def time_steps(dc, steps: int, warmup: int, batched: bool = False):
-    """Run warmup + 2 x steps calls on torch's current stream. After the warmup, a pass of `steps` calls with
-    events after every step and HIP events, handed to the library through timing_start / timing_stop, that
-    bracket the main kernel of every call alone (on the stream the library launches on). Then the timed pass:
-    the same `steps` calls with nothing between them, bracketed by two events and a synchronize on both sides
-    (an event recorded between calls costs several microseconds of a 60-200 us step, so the pass that carries
-    them is not the one that is timed).
-    Returns (total ms of the timed pass, per-step ms and per-step main-kernel ms of the pass with events)."""
+    """Run warmup + 2 x steps calls on torch's current stream. After the warmup, a pass of `steps` calls with HIP
+    events, handed to the library through timing_start / timing_stop, that bracket the main kernel of every call
+    alone (on the stream the library launches on). Then the timed pass: the same `steps` calls with nothing between
+    them, bracketed by two events and a synchronize on both sides (an event recorded between calls costs several
+    microseconds of a 60-200 us step, so the pass that carries them is not the one that is timed).
+    Returns (ms per call of the timed pass, mean main-kernel ms of the pass with events)."""
     import torch
     M = dc.M
     run = M.attn_prefill if dc.prefill else M.attn_decode
@@ -80,17 +84,13 @@ def time_steps(dc, steps: int, warmup: int, batched: bool = False):
     for _ in range(warmup):
         run(dc.params)
     torch.cuda.synchronize()
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     k0 = [M.HipEvent() for _ in range(steps)]
     k1 = [M.HipEvent() for _ in range(steps)]
-    ev[0].record()
     for i in range(steps):
         dc.params.timing_start, dc.params.timing_stop = k0[i].handle, k1[i].handle
         run(dc.params)
-        ev[i + 1].record()
     torch.cuda.synchronize()
     dc.params.timing_start = dc.params.timing_stop = None
-    per = [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]
     kern = [k0[i].elapsed_ms(k1[i]) for i in range(steps)]
     t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
@@ -99,96 +99,307 @@ def time_steps(dc, steps: int, warmup: int, batched: bool = False):
         run(dc.params)
     t1.record()
     torch.cuda.synchronize()
-    return t0.elapsed_time(t1), per, kern
+    return t0.elapsed_time(t1) / steps, sum(kern) / len(kern)
 
 
-def bench_commit(args) -> int:
-    """`--commit`: the commit step alone (scatter of new un-rotated K/V into their pages) on the prompt-commit
-    workload: 64 requests x 1024 new tokens of Llama-3-8B KV shape (Hkv 8, D 128), bf16 pages of 16 slots
-    (`--commit fp8`: e4m3 pages of 32 slots). One JSON line, HBM roofline on source bytes read + page bytes
-    written."""
-    import numpy as np
+def time_cold(dc, n: int = 5) -> float:
+    """Per-call ms with cold caches: a 1 GiB memset (four times the Infinity Cache) runs before every call."""
     import torch
-    import paper_2512_16822_amd as M
-    import workloads as W
-    M.load()
-    fp8 = args.commit == "fp8"
-    kv_dtype, P = ("f8e4m3", 32) if fp8 else ("bf16", 16)
-    Hkv, D, B, T = 8, 128, 64, 1024
-    MB = T // P + 1
-    dev = torch.device("cuda:0")
-    rng = np.random.default_rng(10)
-    pages = W.gen_pages(25, B * MB, Hkv, P, D, kv_dtype)
-    bt = rng.permutation(B * MB).reshape(B, MB).astype(np.int32)
-    i32 = lambda a: torch.tensor(np.asarray(a, dtype=np.int32), dtype=torch.int32, device=dev)
-    src = lambda: torch.from_numpy(rng.standard_normal((B * T, Hkv, D)).astype(np.float32)).to(torch.bfloat16).to(dev)
-    k_new, v_new = src(), src()
-    k_dev, v_dev = pages.k.to(dev), pages.v.to(dev)
-    ks = None if pages.k_scales is None else pages.k_scales.to(dev)
-    vs = None if pages.v_scales is None else pages.v_scales.to(dev)
-    p = M.make_commit_params(k_new, v_new, k_dev, v_dev, i32(bt), i32(np.arange(B)), i32([(b % 3) * 8 for b in range(B)]),
-                             i32(np.arange(B + 1) * T), k_scales=ks, v_scales=vs)
-    for _ in range(args.warmup):
-        M.kv_commit(p)
-    torch.cuda.synchronize()
-    k0 = [M.HipEvent() for _ in range(args.steps)]
-    k1 = [M.HipEvent() for _ in range(args.steps)]
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for i in range(args.steps):
-        p.timing_start, p.timing_stop = k0[i].handle, k1[i].handle
-        M.kv_commit(p)
-    e1.record()
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / args.steps
-    kern_ms = sum(a.elapsed_ms(b) for a, b in zip(k0, k1)) / args.steps
-    n_el = 2 * B * T * Hkv * D
-    abytes = n_el * 2 + n_el * (1 if fp8 else 2) + B * MB * 4 + (B * MB * 8 if fp8 else 0) + (3 * B + 1) * 4
-    ach = abytes / (kern_ms * 1e-3) / 1e9
-    print(json.dumps(dict(metric="KV commit throughput (source read + page write)", value=abytes / (ms * 1e-3) / 1e9,
-                          unit="GB/s", n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms,
-                          higher_is_better=True, scaling="weak", vs_baseline=None,
-                          dtype="bf16 -> e4m3" if fp8 else "bf16", data="synthetic",
-                          config=dict(workload=f"prompt_commit_64x1024_llama3_8b_{kv_dtype}", B=B, new_tokens=B * T,
-                                      Hkv=Hkv, D=D, P=P, algorithmic_bytes=abytes),
-                          roofline=dict(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS,
-                                        traffic=None, kernel="kv_commit", kernel_ms=kern_ms), cpu_baseline=None)))
-    return 0
+    run = dc.M.attn_prefill if dc.prefill else dc.M.attn_decode
+    flush = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    ms = []
+    for _ in range(n):
+        flush.zero_()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        run(dc.params)
+        e1.record()
+        torch.cuda.synchronize()
+        ms.append(e0.elapsed_time(e1))
+    del flush
+    return sum(ms) / len(ms)
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=2, help="BASELINE.json config (1-based); default 2")
-    ap.add_argument("--layout", default="both", choices=["both", "shared", "duplicated"])
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rows", type=int, default=0, help="oracle sample size in (token, head) rows")
-    ap.add_argument("--copy-probe", action="store_true",
-                    help="also run a plain 1 GiB device copy three times (calibrates the FETCH_SIZE / WRITE_SIZE "
-                         "counters of a rocprofv3 --pmc run of this same command)")
-    ap.add_argument("--commit", nargs="?", const="bf16", default=None, choices=["bf16", "fp8"],
-                    help="benchmark the commit step (mepic_kv_commit) instead of attention")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
-              file=sys.stderr)
-        return 2
+def oracle_sample(case, got, n_rows_total, cpu_seconds, prefill, flops, abytes):
+    """The oracle as it stands on this machine's host cores, on a bounded random sample of (query token, head) rows of the
+    same workload; also a live parity check of the timed output."""
+    import numpy as np
+    from oracle import attn as oracle_attn
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from harness import oracle_out
+    st = case.st
+    # ~0.15 us per (row, key) at D = 128 on the 16 host cores of a GPU box
+    per_row = 0.15e-6 * max(1.0, float(case.kv_lens.mean()))
+    n_rows = max(8, min(n_rows_total, int(cpu_seconds / per_row)))
+    if n_rows >= n_rows_total:
+        rows = [(t, h) for t in range(case.n_q) for h in range(st.Hq)]
+    else:
+        rng = np.random.default_rng(0)
+        rows = sorted({(int(rng.integers(case.n_q)), int(rng.integers(st.Hq))) for _ in range(n_rows)})
+    t0 = time.perf_counter()
+    want = oracle_out(oracle_attn, case, rows=rows)
+    cpu_s = time.perf_counter() - t0
+    err = float(np.abs(np.stack([got[t, h] for t, h in rows]) - want).max())
+    whole = cpu_s * n_rows_total / len(rows)
+    return dict(value=(flops / whole / 1e12) if prefill else (abytes / whole / 1e9), unit="TFLOP/s" if prefill else "GB/s",
+                cores=oracle_attn.num_threads(), kind="oracle",
+                sample=f"{len(rows)} of {n_rows_total} (query token, head) rows in {cpu_s:.2f} s, scaled to the whole job",
+                max_abs_err_of_gpu_on_sample=err)
 
-    if args.commit:
-        return bench_commit(args)
 
+def bench_attention(cfg: int, args, mfma_measured=None) -> dict:
+    """One BASELINE attention workload: every layout and call variant, its roofline record, the oracle beside it."""
     import numpy as np
     import torch
     import paper_2512_16822_amd as M
     import workloads as W
     from paper_2512_16822_amd.device_case import DeviceCase, align_with_library
 
+    st = W.config(cfg)
+    t0 = time.perf_counter()
+    aligned, pool = align_with_library(M, st)
+    align_s = time.perf_counter() - t0
+    stats = pool.stats()
+    case = W.assemble(st, aligned, poison=False)
+    prefill = st.mode == "prefill"
+    abytes, ubytes = algorithmic_bytes(case), case.kv_bytes_unique()
+    flops = 4 * st.D * visible_pairs(case) * st.Hq
+    rec = dict(workload=st.name, B=st.B, Hq=st.Hq, Hkv=st.Hkv, D=st.D, P=st.P, kv_len_mean=float(case.kv_lens.mean()),
+               kv_len_max=int(case.kv_lens.max()), n_q_tokens=case.n_q, algorithmic_bytes=abytes,
+               unique_kv_bytes=ubytes, useful_flops=flops,
+               dtype={"f32": "f32", "bf16": "bf16", "f8e4m3": "bf16 (fp8 e4m3 KV)"}[st.kv_dtype],
+               accounting=dict(pages_unique=stats["pages_in_use_unique"], pages_duplicated=stats["pages_logical_duplicated"],
+                               ratio=stats["pages_logical_duplicated"] / max(1, stats["pages_in_use_unique"]),
+                               aligner_us_per_request=align_s / max(1, st.B) * 1e6))
+    gbs = lambda nbytes, ms: nbytes / (ms * 1e-3) / 1e9
+    layouts = {}
+
+    # ---- page-sharing layout (the workload as named): pages shared between requests come from the caches ----
+    dc = DeviceCase(M, case)
+    call_ms, kern_ms = time_steps(dc, args.steps, args.warmup)
+    kernel = M.last_kernel()
+    shared_out = dc.out.float().cpu()
+    if prefill:
+        layouts["shared"] = dict(call_ms=call_ms, kernel_ms=kern_ms, kernel=kernel, tflops=flops / (call_ms * 1e-3) / 1e12)
+        if not args.no_cold:
+            layouts["shared"]["cold_call_ms"] = time_cold(dc)
+    else:
+        layouts["shared"] = dict(call_ms=call_ms, kernel_ms=kern_ms, kernel=kernel, bound="cache",
+                                 gbs_logical=gbs(abytes, call_ms), gbs_unique=gbs(ubytes, call_ms),
+                                 note="pages many requests alias are served from L2 / Infinity Cache: not an HBM rate")
+        if not args.no_cold:
+            layouts["shared"]["cold_call_ms"] = time_cold(dc)
+        if kernel.startswith("decode_mfma"):
+            # the same job with one pass over shared pages for several requests (plan built on the host)
+            fmt = M.F8E4M3 if st.kv_dtype == "f8e4m3" else M.BF16
+            info = dc.prepare_batched()
+            plan_s = min(_timed(lambda: M.decode_plan_build(case.block_tables, case.kv_lens, st.P, st.Hq, st.Hkv, fmt))
+                         for _ in range(3))
+            b_ms, b_kern = time_steps(dc, args.steps, args.warmup, batched=True)
+            diff = (dc.out.float().cpu() - shared_out).abs().max().item()
+            assert diff <= 4e-2, f"batched and plain decode disagree by {diff}"
+            batched = dict(call_ms=b_ms, kernel_ms=b_kern, kernel=M.last_kernel(), bound="cache",
+                           gbs_logical=gbs(abytes, b_ms), gbs_unique=gbs(ubytes, b_ms), plan=info.as_dict(),
+                           plan_build_ms=plan_s * 1e3)
+            # A plan built ahead serves PLAN_HORIZON decode steps of all N_LAYERS layers. Measured half-way through its
+            # horizon: built from kv_lens - H/2, used at kv_lens.
+            half = PLAN_HORIZON // 2
+            early = np.maximum(case.kv_lens - half, 0).astype(np.int32)
+            build = lambda: M.decode_plan_build(case.block_tables, early, st.P, st.Hq, st.Hkv, fmt, horizon_tokens=PLAN_HORIZON)
+            ahead_s = min(_timed(build) for _ in range(3))
+            plan, ainfo = build()
+            dc.plan_info, dc.plan = ainfo, torch.from_numpy(plan).to(dc.q.device)
+            nbytes = M.attn_decode_batched_workspace_size(dc.params, ainfo)
+            if nbytes > dc.ws.numel():
+                dc.ws = torch.empty(nbytes, dtype=torch.uint8, device=dc.q.device)
+                dc.params.workspace, dc.params.workspace_bytes = dc.ws.data_ptr(), nbytes
+            a_ms, _ = time_steps(dc, args.steps, args.warmup, batched=True)
+            diff = (dc.out.float().cpu() - shared_out).abs().max().item()
+            assert diff <= 4e-2, f"batched decode with a plan built ahead and plain decode disagree by {diff}"
+            amort_us = ahead_s * 1e6 / (PLAN_HORIZON * N_LAYERS)
+            batched["plan_ahead"] = dict(horizon_steps=PLAN_HORIZON, layers_sharing_a_plan=N_LAYERS, build_ms=ahead_s * 1e3,
+                                         call_ms=a_ms, amortised_plan_us_per_call=amort_us,
+                                         end_to_end_us_per_call=a_ms * 1e3 + amort_us, plain_call_us=call_ms * 1e3,
+                                         gain_us_per_call=call_ms * 1e3 - (a_ms * 1e3 + amort_us))
+            layouts["shared_batched"] = batched
+    del dc
+    torch.cuda.empty_cache()
+
+    # ---- one page per logical block: every byte comes from HBM (decode: the layout the HBM roofline is quoted on) ----
+    if prefill:
+        traffic = MEASURED_TRAFFIC.get((f"cfg{cfg}", kernel))
+        ach = flops / (kern_ms * 1e-3) / 1e12
+        roofline = dict(bound="mfma", achieved=ach, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s", frac=ach / MFMA_BF16_PEAK_TFLOPS,
+                        traffic=traffic, layout="shared", kernel=kernel, kernel_ms=kern_ms, call_ms=call_ms,
+                        frac_call=flops / (call_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS)
+        if mfma_measured:
+            roofline["peak_measured"] = mfma_measured
+            roofline["frac_of_measured"] = ach / mfma_measured
+        main = dict(value=flops / (call_ms * 1e-3) / 1e12, unit="TFLOP/s", ms=call_ms, layout="shared",
+                    metric="fused-RoPE paged prefill attention throughput")
+    else:
+        dup = W.to_duplicated(case)
+        dch = DeviceCase(M, dup, flags=M.FLAG_KV_READ_ONCE)   # no page is shared: the caller says so
+        h_ms, h_kern = time_steps(dch, args.steps, args.warmup)
+        assert torch.equal(dch.out.float().cpu(), shared_out), "layouts disagree"
+        layouts["duplicated_read_once_hint"] = dict(call_ms=h_ms, kernel_ms=h_kern, kernel=M.last_kernel(), bound="hbm",
+                                                    gbs=gbs(abytes, h_ms), frac_call=gbs(abytes, h_ms) / HBM_PEAK_GBS,
+                                                    frac_kernel=gbs(abytes, h_kern) / HBM_PEAK_GBS)
+        if not args.no_cold:
+            layouts["duplicated_read_once_hint"]["cold_call_ms"] = time_cold(dch)
+        del dch
+        dcn = DeviceCase(M, dup)
+        n_ms, n_kern = time_steps(dcn, args.steps, args.warmup)
+        layouts["duplicated"] = dict(call_ms=n_ms, kernel_ms=n_kern, kernel=M.last_kernel(), bound="hbm", gbs=gbs(abytes, n_ms),
+                                     frac_call=gbs(abytes, n_ms) / HBM_PEAK_GBS, frac_kernel=gbs(abytes, n_kern) / HBM_PEAK_GBS)
+        del dcn, dup
+        torch.cuda.empty_cache()
+        ach = gbs(abytes, h_kern)
+        roofline = dict(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS,
+                        traffic=MEASURED_TRAFFIC.get((f"cfg{cfg}", kernel)), layout="duplicated_read_once_hint",
+                        kernel=kernel, kernel_ms=h_kern, call_ms=h_ms, frac_call=gbs(abytes, h_ms) / HBM_PEAK_GBS,
+                        frac_without_hint=gbs(abytes, n_kern) / HBM_PEAK_GBS)
+        main = dict(value=gbs(abytes, h_ms), unit="GB/s", ms=h_ms, layout="duplicated_read_once_hint",
+                    metric="fused-RoPE paged decode attention KV throughput")
+    rec.update(layouts=layouts, roofline=roofline, main=main)
+    rec["cpu_baseline"] = None if args.no_cpu_baseline else oracle_sample(
+        case, shared_out.double().numpy(), case.n_q * st.Hq, args.cpu_seconds, prefill, flops, abytes)
+    return rec
+
+
+def _timed(f) -> float:
+    t0 = time.perf_counter()
+    f()
+    return time.perf_counter() - t0
+
+
+def bench_commit(kind: str, args) -> dict:
+    """The commit step alone (scatter of new un-rotated K/V into their pages), Llama-3-8B KV shape (Hkv 8, D 128):
+    `bf16` / `fp8`: 64 requests x 1024 new tokens into bf16 pages of 16 slots / e4m3 pages of 32 slots (prompt commit);
+    `decode`: 4096 requests x one token into bf16 pages (what a decode step of a large batch commits per layer).
+    HBM roofline on source bytes read + page bytes written."""
+    import numpy as np
+    import torch
+    import paper_2512_16822_amd as M
+    import workloads as W
+    fp8 = kind == "fp8"
+    kv_dtype, P = ("f8e4m3", 32) if fp8 else ("bf16", 16)
+    Hkv, D = 8, 128
+    B, T = (4096, 1) if kind == "decode" else (64, 1024)
+    MB = 2 if kind == "decode" else T // P + 1
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(10)
+    pages = W.gen_pages(25, B * MB, Hkv, P, D, kv_dtype)
+    bt = rng.permutation(B * MB).reshape(B, MB).astype(np.int32)
+    i32 = lambda a: torch.tensor(np.asarray(a, dtype=np.int32), dtype=torch.int32, device=dev)
+    src_cpu = lambda: torch.from_numpy(rng.standard_normal((B * T, Hkv, D)).astype(np.float32)).to(torch.bfloat16)
+    k_cpu, v_cpu = src_cpu(), src_cpu()
+    k_new, v_new = k_cpu.to(dev), v_cpu.to(dev)
+    k_dev, v_dev = pages.k.to(dev), pages.v.to(dev)
+    ks = None if pages.k_scales is None else pages.k_scales.to(dev)
+    vs = None if pages.v_scales is None else pages.v_scales.to(dev)
+    first = [int(rng.integers(P)) for _ in range(B)] if kind == "decode" else [(b % 3) * 8 for b in range(B)]
+    p = M.make_commit_params(k_new, v_new, k_dev, v_dev, i32(bt), i32(np.arange(B)), i32(first), i32(np.arange(B + 1) * T),
+                             k_scales=ks, v_scales=vs)
+    for _ in range(args.warmup):
+        M.kv_commit(p)
+    torch.cuda.synchronize()
+    k0 = [M.HipEvent() for _ in range(args.steps)]
+    k1 = [M.HipEvent() for _ in range(args.steps)]
+    for i in range(args.steps):
+        p.timing_start, p.timing_stop = k0[i].handle, k1[i].handle
+        M.kv_commit(p)
+    torch.cuda.synchronize()
+    p.timing_start = p.timing_stop = None
+    kern_ms = sum(a.elapsed_ms(b) for a, b in zip(k0, k1)) / args.steps
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        M.kv_commit(p)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    n_el = 2 * B * T * Hkv * D
+    blocks_touched = B * (-(-(max(first) + T) // P))
+    abytes = n_el * 2 + n_el * (1 if fp8 else 2) + blocks_touched * 4 + (blocks_touched * 8 if fp8 else 0) + (3 * B + 1) * 4
+    ach = abytes / (kern_ms * 1e-3) / 1e9
+    rec = dict(workload=f"commit_{kind}_{B}x{T}_llama3_8b_{kv_dtype}", B=B, new_tokens=B * T, Hkv=Hkv, D=D, P=P,
+               dtype="bf16 -> e4m3" if fp8 else "bf16", algorithmic_bytes=abytes, call_ms=ms,
+               main=dict(value=abytes / (ms * 1e-3) / 1e9, unit="GB/s", ms=ms, layout="private pages",
+                         metric="KV commit throughput (source read + page write)"),
+               roofline=dict(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS,
+                             traffic=MEASURED_TRAFFIC.get((f"commit_{kind}", "kv_commit")), kernel="kv_commit",
+                             kernel_ms=kern_ms, call_ms=ms, frac_call=abytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS))
+    rec["cpu_baseline"] = None
+    if not args.no_cpu_baseline:
+        from oracle import commit as oracle_commit
+        n_runs = {"bf16": 32, "fp8": 16, "decode": B}[kind]     # a bounded share of the runs, scaled to the whole job
+        raw = lambda t: t.view(torch.uint8 if t.dtype == torch.float8_e4m3fn else torch.uint16).numpy().reshape(-1).copy()
+        k_ref, v_ref = raw(pages.k), raw(pages.v)
+        cu = np.arange(n_runs + 1) * T
+        t0 = time.perf_counter()
+        oracle_commit.kv_commit(k_ref, v_ref, None if not fp8 else pages.k_scales.numpy(),
+                                None if not fp8 else pages.v_scales.numpy(),
+                                k_cpu.view(torch.uint16).numpy()[: n_runs * T], v_cpu.view(torch.uint16).numpy()[: n_runs * T],
+                                bt, list(range(n_runs)), first[:n_runs], cu, Hkv=Hkv, D=D, P=P, kv_dtype=kv_dtype)
+        cpu_s = time.perf_counter() - t0
+        whole = cpu_s * B / n_runs
+        rec["cpu_baseline"] = dict(value=abytes / whole / 1e9, unit="GB/s", cores=1, kind="oracle",
+                                   sample=f"{n_runs} of {B} runs ({n_runs * T} tokens) in {cpu_s:.2f} s, scaled to the whole job")
+    return rec
+
+
+def bench_mfma_probe(args) -> dict:
+    """The matrix-instruction-only kernel: what the chip sustains on v_mfma_f32_32x32x16_bf16 with every CU busy."""
+    import torch
+    import paper_2512_16822_amd as M
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    iters = 20000
+    for _ in range(2):
+        M.probe_mfma_bf16(iters, sink)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    flop = 0.0
+    for _ in range(5):
+        flop += M.probe_mfma_bf16(iters, sink)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1)
+    tf = flop / (ms * 1e-3) / 1e12
+    return dict(workload="mfma_only_bf16_32x32x16", tflops=tf, frac_of_nominal=tf / MFMA_BF16_PEAK_TFLOPS, ms=ms / 5,
+                main=dict(value=tf, unit="TFLOP/s", ms=ms / 5, layout="registers only", metric="matrix-instruction-only rate"),
+                roofline=dict(bound="mfma", achieved=tf, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s", frac=tf / MFMA_BF16_PEAK_TFLOPS,
+                              traffic=None, kernel="mfma_rate", kernel_ms=ms / 5), cpu_baseline=None)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--only", default="", help="comma-separated records to run (default: all): " + " ".join(ALL))
+    ap.add_argument("--config", type=int, default=0, help="shorthand for --only cfgN")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cold", action="store_true", help="skip the cold-cache timings")
+    ap.add_argument("--cpu-seconds", type=float, default=4.0, help="oracle time per attention record, about")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain 1 GiB device copy three times (calibrates the FETCH_SIZE / WRITE_SIZE "
+                         "counters of a rocprofv3 --pmc run of this same command)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+    names = [n for n in (args.only.split(",") if args.only else ([f"cfg{args.config}"] if args.config else ALL)) if n]
+    bad = [n for n in names if n not in ALL]
+    if bad:
+        print(f"bench.py: unknown record(s) {bad}; known: {ALL}", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2512_16822_amd as M
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     M.load()
-    st = W.config(args.config)
-
     if args.copy_probe:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -198,115 +409,35 @@ def main() -> int:
         del src, dst
         torch.cuda.empty_cache()
 
-    # ---- scheduling path (host): align every request, report the accounting ----
-    t0 = time.perf_counter()
-    aligned, pool = align_with_library(M, st)
-    align_s = time.perf_counter() - t0
-    stats = pool.stats()
-    case = W.assemble(st, aligned, poison=False)
-    prefill = st.mode == "prefill"
-
-    results = {}
-    layouts = ["shared", "duplicated"] if args.layout == "both" else [args.layout]
-    for layout in layouts:
-        c = case if layout == "shared" else W.to_duplicated(case)
-        # one page per logical block: no page is shared, which the caller tells the library (MEPIC_FLAG_KV_READ_ONCE)
-        dc = DeviceCase(M, c, flags=0 if layout == "shared" else M.FLAG_KV_READ_ONCE)
-        total_ms, per, kern = time_steps(dc, args.steps, args.warmup)
-        results[layout] = dict(ms=total_ms / args.steps, min_ms=min(per), kernel=M.last_kernel(),
-                               kernel_ms=sum(kern) / len(kern), ms_instr=sum(per) / len(per),
-                               pages=c.pages.num_pages, out=dc.out.float().cpu())
-        if layout == "shared" and not prefill and M.last_kernel().startswith("decode_mfma"):
-            # the same job with one pass over shared pages for several requests (plan built on the host)
-            info = dc.prepare_batched()
-            plan_s = 1e9
-            for _ in range(3):   # the host planner alone (the upload and the workspace are not part of it)
-                t0 = time.perf_counter()
-                M.decode_plan_build(c.block_tables, c.kv_lens, st.P, st.Hq, st.Hkv,
-                                    M.F8E4M3 if st.kv_dtype == "f8e4m3" else M.BF16)
-                plan_s = min(plan_s, time.perf_counter() - t0)
-            total_ms, per, kern = time_steps(dc, args.steps, args.warmup, batched=True)
-            results["shared_batched"] = dict(ms=total_ms / args.steps, min_ms=min(per), kernel=M.last_kernel(),
-                                             kernel_ms=sum(kern) / len(kern), ms_instr=sum(per) / len(per),
-                                             pages=c.pages.num_pages,
-                                             out=dc.out.float().cpu(), plan=info.as_dict(), plan_build_ms=plan_s * 1e3)
-        del dc
-        torch.cuda.empty_cache()
-    if "shared_batched" in results:
-        diff = (results["shared_batched"]["out"] - results["shared"]["out"]).abs().max().item()
-        assert diff <= 4e-2, f"batched and plain decode disagree by {diff}"
-    if len(layouts) == 2:
-        assert torch.equal(results["shared"]["out"], results["duplicated"]["out"]), "layouts disagree"
-
-    abytes = algorithmic_bytes(case)
-    flops = 4 * st.D * visible_pairs(case) * st.Hq
-    main_layout = "shared" if "shared" in results else layouts[0]
-    roof_layout = "duplicated" if "duplicated" in results else layouts[0]
-    ms = results[main_layout]["ms"]
-    if prefill:
-        value, unit, metric = flops / (ms * 1e-3) / 1e12, "TFLOP/s", "fused-RoPE paged prefill attention throughput"
-        roof_layout = main_layout          # bound by the matrix cores: where the pages come from does not matter
-        rms = results[roof_layout]["kernel_ms"]
-        ach = flops / (rms * 1e-3) / 1e12
-        traffic = MEASURED_TRAFFIC.get((st.name, roof_layout, results[roof_layout]["kernel"]))
-        roofline = dict(bound="mfma", achieved=ach, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
-                        frac=ach / MFMA_BF16_PEAK_TFLOPS, traffic=traffic, layout=roof_layout,
-                        kernel=results[roof_layout]["kernel"], kernel_ms=rms, call_ms=results[roof_layout]["ms"])
-    else:
-        value, unit, metric = abytes / (ms * 1e-3) / 1e9, "GB/s", "fused-RoPE paged decode attention KV throughput"
-        rms = results[roof_layout]["kernel_ms"]
-        ach = abytes / (rms * 1e-3) / 1e9
-        traffic = MEASURED_TRAFFIC.get((st.name, roof_layout, results[roof_layout]["kernel"]))
-        roofline = dict(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS,
-                        traffic=traffic, layout=roof_layout, kernel=results[roof_layout]["kernel"], kernel_ms=rms,
-                        call_ms=results[roof_layout]["ms"])
-
-    # ---- the oracle on this machine's host cores, on a bounded sample of the same workload ----
-    cpu = None
-    if not args.no_cpu_baseline:
-        from oracle import attn as oracle_attn
-        from oracle import align as oracle_align
-        from harness import oracle_out
-        opool = oracle_align.PoolOracle(1 << 20, st.P)
-        o_aligned = [opool.align(segs, st.extra_tail) for segs in st.requests]
-        assert all(a["block_table"] == b["block_table"].tolist() for a, b in zip(o_aligned, aligned))
-        n_rows_total = case.n_q * st.Hq
-        # 10-20 CPU-seconds of oracle work: ~0.15 us per (row, key) at D = 128 on the 16 host cores of a GPU machine
-        n_rows = args.cpu_rows or max(8, min(n_rows_total, int(1.0e8 / max(1, int(case.kv_lens.mean())))))
-        if n_rows >= n_rows_total:                    # the whole job is within the budget: no sampling
-            rows = [(t, h) for t in range(case.n_q) for h in range(st.Hq)]
-        else:
-            rng = np.random.default_rng(0)
-            rows = sorted({(int(rng.integers(case.n_q)), int(rng.integers(st.Hq))) for _ in range(n_rows)})
+    t_all = time.perf_counter()
+    records = {}
+    mfma = None
+    if "mfma_probe" in names or "cfg3" in names:
+        records["mfma_probe"] = bench_mfma_probe(args)
+        mfma = records["mfma_probe"]["tflops"]
+    for n in names:
         t0 = time.perf_counter()
-        want = oracle_out(oracle_attn, case, rows=rows)
-        cpu_s = time.perf_counter() - t0
-        got = results[main_layout]["out"].double().numpy()
-        err = float(np.abs(np.stack([got[t, h] for t, h in rows]) - want).max())
-        scale = n_rows_total / len(rows)
-        whole = cpu_s * scale
-        cpu = dict(value=(flops / whole / 1e12) if prefill else (abytes / whole / 1e9), unit=unit,
-                   cores=oracle_attn.num_threads(), kind="oracle",
-                   sample=f"{len(rows)} of {n_rows_total} (query token, head) rows in {cpu_s:.2f} s, scaled to the whole job",
-                   max_abs_err_of_gpu_on_sample=err)
-
-    line = dict(metric=metric, value=value, unit=unit, n_gpus=1, steps=args.steps, warmup=args.warmup,
-                ms_per_step=ms, higher_is_better=True, scaling="weak", vs_baseline=None,
-                dtype={"f32": "f32", "bf16": "bf16", "f8e4m3": "bf16 (fp8 e4m3 KV)"}[st.kv_dtype],
-                data="synthetic",
-                config=dict(workload=st.name, layout=main_layout, B=st.B, Hq=st.Hq, Hkv=st.Hkv, D=st.D, P=st.P,
-                            kv_len_mean=float(case.kv_lens.mean()), kv_len_max=int(case.kv_lens.max()),
-                            n_q_tokens=case.n_q, algorithmic_bytes=abytes, useful_flops=flops),
-                roofline=roofline, cpu_baseline=cpu,
-                layouts={k: dict(ms_per_step=v["ms"], ms_per_step_with_events=v["ms_instr"], min_ms=v["min_ms"],
-                                 kernel_ms=v["kernel_ms"], pages=v["pages"],
-                                 kernel=v["kernel"], gbs=abytes / (v["ms"] * 1e-3) / 1e9,
-                                 **({"plan": v["plan"], "plan_build_ms": v["plan_build_ms"]} if "plan" in v else {}))
-                         for k, v in results.items()},
-                accounting=dict(pages_unique=stats["pages_in_use_unique"],
-                                pages_duplicated=stats["pages_logical_duplicated"],
-                                ratio=stats["pages_logical_duplicated"] / max(1, stats["pages_in_use_unique"]),
-                                aligner_us_per_request=align_s / max(1, st.B) * 1e6))
+        if n.startswith("cfg"):
+            records[n] = bench_attention(int(n[3:]), args, mfma_measured=mfma)
+        elif n.startswith("commit_"):
+            records[n] = bench_commit(n[len("commit_"):], args)
+        if n in records:
+            records[n]["bench_wall_s"] = round(time.perf_counter() - t0, 2)
+    first = records[names[0]]
+    m = first.pop("main")
+    for r in records.values():
+        r.pop("main", None)
+    line = dict(metric=m["metric"], value=m["value"], unit=m["unit"], n_gpus=1, steps=args.steps, warmup=args.warmup,
+                ms_per_step=m["ms"], higher_is_better=True, scaling="weak", vs_baseline=None,
+                dtype=first.get("dtype", "bf16"), data="synthetic",
+                config={"workload": first["workload"], "layout": m["layout"],
+                        **{k: first[k] for k in ("B", "Hq", "Hkv", "D", "P", "kv_len_mean", "kv_len_max", "n_q_tokens",
+                                                 "algorithmic_bytes", "unique_kv_bytes", "useful_flops", "new_tokens") if k in first}},
+                roofline=first["roofline"], cpu_baseline=first.get("cpu_baseline"),
+                layouts=first.get("layouts"), accounting=first.get("accounting"),
+                mfma_peak=dict(nominal_tflops=MFMA_BF16_PEAK_TFLOPS, measured_tflops=mfma) if mfma else None,
+                configs={k: v for k, v in records.items() if k != names[0]},
+                bench_wall_s=round(time.perf_counter() - t_all, 1))
     print(json.dumps(line))
     return 0
 

@@ -249,6 +249,16 @@ int mepic_attn_prefill(const mepic_attn_params* params, void* hip_stream);
 const char* mepic_last_kernel(void);
 
 /*
+ * Calibration of the matrix-core roofline, for benchmarks (not part of the method): launches a kernel that does
+ * nothing but the bf16 matrix instruction of the prefill kernel (v_mfma_f32_32x32x16_bf16; four independent
+ * accumulators per wave, two waves per SIMD, one workgroup per compute unit, `iters` rounds of four products) and
+ * writes the floating-point operations it executes to *flop_out (host). The caller times it with events on the
+ * stream: flop / time is the rate the device sustains on that instruction, to be read next to the nominal peak.
+ * sink_device: device float[1] (never written in practice). Errors: MEPIC_ERR_INVALID, MEPIC_ERR_LAUNCH.
+ */
+int mepic_probe_mfma_bf16(int32_t iters, float* sink_device, double* flop_out, void* hip_stream);
+
+/*
  * Self-test of one building block, for the test suite (a guard against toolchain changes, not part of the method):
  * the bf16 decode kernel rotates K (§3.3.3) with two-term dot-product instructions issued as a hand-written block
  * whose hazard rules the compiler does not see. This call runs that block alone. words_device: device uint32

@@ -27,7 +27,7 @@ EXPORTS = ["mepic_strerror", "mepic_version", "mepic_pool_create", "mepic_pool_d
            "mepic_attn_decode", "mepic_attn_prefill", "mepic_last_kernel", "mepic_kv_commit",
            "mepic_decode_plan_capacity", "mepic_decode_plan_build", "mepic_attn_decode_batched_workspace_size",
            "mepic_attn_decode_batched", "mepic_attn_decode_noalloc", "mepic_selftest_dot_rotation",
-           "mepic_decode_plan_build_ahead"]
+           "mepic_decode_plan_build_ahead", "mepic_probe_mfma_bf16"]
 
 
 class MepicError(RuntimeError):
@@ -115,6 +115,7 @@ def load() -> ctypes.CDLL:
     lib.mepic_attn_decode.argtypes = [ctypes.POINTER(AttnParams), ctypes.c_void_p]
     lib.mepic_attn_prefill.argtypes = [ctypes.POINTER(AttnParams), ctypes.c_void_p]
     lib.mepic_attn_decode_noalloc.argtypes = [ctypes.POINTER(AttnParams), ctypes.c_void_p]
+    lib.mepic_probe_mfma_bf16.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
     lib.mepic_selftest_dot_rotation.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p]
     lib.mepic_kv_commit.argtypes = [ctypes.POINTER(CommitParams), ctypes.c_void_p]
     lib.mepic_decode_plan_capacity.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
@@ -279,6 +280,15 @@ def attn_decode_noalloc(params: AttnParams, stream=None) -> None:
     rc = load().mepic_attn_decode_noalloc(ctypes.byref(params), _stream_handle(stream))
     if rc != OK:
         raise MepicError(rc, "mepic_attn_decode_noalloc")
+
+
+def probe_mfma_bf16(iters: int, sink, stream=None) -> float:
+    """mepic_probe_mfma_bf16: launches the matrix-instruction-only kernel; returns the flop it executes."""
+    flop = ctypes.c_double()
+    rc = load().mepic_probe_mfma_bf16(iters, _p(sink), ctypes.byref(flop), _stream_handle(stream))
+    if rc != OK:
+        raise MepicError(rc, "mepic_probe_mfma_bf16")
+    return float(flop.value)
 
 
 def selftest_dot_rotation(words, out, stream=None) -> None:

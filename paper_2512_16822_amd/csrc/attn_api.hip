@@ -290,6 +290,15 @@ int mepic_attn_prefill(const mepic_attn_params* params, void* hip_stream) {
 
 const char* mepic_last_kernel(void) { return mepic::g_last_kernel; }
 
+int mepic_probe_mfma_bf16(int32_t iters, float* sink_device, double* flop_out, void* hip_stream) {
+  if (iters < 0 || !sink_device || !flop_out) return MEPIC_ERR_INVALID;
+  const int n_wg = mepic::device_compute_units();
+  // per workgroup: 8 waves x iters x 4 products of 32 x 32 x 16 multiply-adds
+  *flop_out = (double)n_wg * 8.0 * (double)iters * 4.0 * (2.0 * 32 * 32 * 16);
+  const hipError_t e = mepic::launch_mfma_rate_probe(iters, sink_device, n_wg, reinterpret_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? MEPIC_OK : MEPIC_ERR_LAUNCH;
+}
+
 int mepic_selftest_dot_rotation(const uint32_t* words_device, float* out_device, int32_t n, void* hip_stream) {
   if (n < 0 || (n && (!words_device || !out_device))) return MEPIC_ERR_INVALID;
   if (n == 0) return MEPIC_OK;

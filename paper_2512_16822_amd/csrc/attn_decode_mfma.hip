@@ -1018,6 +1018,8 @@ hipError_t launch_decode_mfma_batched(const AttnArgs& a, int n_runs, hipStream_t
 // kernel's static tables in the 64 KB a workgroup gets without asking for more.
 int decode_mfma_max_requests() { return (64 * 1024 - 44 * 1024) / (int)sizeof(int) - 1; }
 
+int device_compute_units() { return compute_units(); }
+
 hipError_t launch_dot_rotate_selftest(const uint32_t* words, float* out, int n, hipStream_t s) {
   hipLaunchKernelGGL(dot_rotate_selftest_kernel, dim3((n + 255) / 256), dim3(256), 0, s, words, out, n);
   return hipGetLastError();
