@@ -37,9 +37,13 @@ PLAN_HORIZON = 32        # decode steps one plan built ahead serves
 # (counter readings in KiB, each scaled by what the same counter reads for a 1 GiB device copy: FETCH_SIZE x2.000,
 # WRITE_SIZE x1.000). Summaries with the commands are under profiles/.
 MEASURED_TRAFFIC = {
-    ("cfg2", "decode_mfma_bf16"): int((583510.4 * 2.0 + 5221.6) * 1024),
-    ("cfg4", "decode_mfma_bf16"): int((1112407.2 * 2.0 + 4236.3) * 1024),
-    ("cfg5", "decode_mfma_fp8"): int((1119965.7 * 2.0 + 9261.2) * 1024),
+    ("cfg2", "decode_mfma_bf16"): int((583732.7 * 2.0 + 5221.9) * 1024),
+    ("cfg4", "decode_mfma_bf16"): int((1115387.0 * 2.0 + 4236.3) * 1024),
+    ("cfg5", "decode_mfma_fp8"): int((1124668.5 * 2.0 + 9258.6) * 1024),
+    ("cfg3", "prefill_mfma_bf16"): int((424860.0 * 2.0 + 34816.0) * 1024),
+    ("commit_bf16", "kv_commit"): int((131422.3 * 2.0 + 276860.1) * 1024),
+    ("commit_fp8", "kv_commit"): int((131385.7 * 2.0 + 174081.0) * 1024),
+    ("commit_decode", "kv_commit"): int((8283.7 * 2.0 + 147456.0) * 1024),
 }
 ALL = ["cfg2", "cfg3", "cfg4", "cfg5", "commit_bf16", "commit_fp8", "commit_decode", "mfma_probe"]
 
