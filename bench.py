@@ -3,7 +3,7 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--only NAME[,NAME..]] [--no-cpu-baseline]
 
-With no flags it measures every workload of the benchmark spec that fits a roofline (configs 2, 3, 4, 5), the commit step
+With no flags it measures every benchmark workload that fits a roofline (configs 2, 3, 4, 5), the commit step
 (prompt shape in bf16 and bf16 -> e4m3, decode-step shape) and the matrix-instruction-only calibration kernel, and
 prints ONE JSON line. A step is one call of the library over the whole batch of the workload (gather through the
 block tables, rotary embedding of K and Q on chip, online softmax, PV, split-K combine), every input already
@@ -152,7 +152,7 @@ def oracle_sample(case, got, n_rows_total, cpu_seconds, prefill, flops, abytes):
 
 
 def bench_attention(cfg: int, args, mfma_measured=None) -> dict:
-    """One BASELINE attention workload: every layout and call variant, its roofline record, the oracle beside it."""
+    """One benchmark attention workload: every layout and call variant, its roofline record, the oracle beside it."""
     import numpy as np
     import torch
     import paper_2512_16822_amd as M

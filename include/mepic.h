@@ -232,7 +232,7 @@ int mepic_attn_decode(const mepic_attn_params* params, void* hip_stream);
  * ends); params->workspace and workspace_bytes are ignored. Same kernels, same result bit for bit as
  * mepic_attn_decode with a workspace. Calls no hipMalloc / hipFree nor any allocating routine.
  * MEPIC_ERR_CAPACITY when mepic_attn_workspace_size for these shapes exceeds MEPIC_NOALLOC_SCRATCH_BYTES
- * (the BASELINE-sized decode batches need 17-32 MB); otherwise the errors of mepic_attn_decode.
+ * (the decode batches of the benchmark workloads need 17-32 MB); otherwise the errors of mepic_attn_decode.
  * All calls on one GPU share that GPU's array: two such calls that overlap in time on one GPU (different
  * streams, different threads) race; calls on one stream are ordered and safe.
  */

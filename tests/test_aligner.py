@@ -214,7 +214,7 @@ def test_library_error_paths():
 
 
 def test_expected_sharing_ratios_of_the_synthetic_configs():
-    """Accounting row: unique vs duplicated pages (the paper's HBM-usage effect, §4) on the BASELINE shapes."""
+    """Accounting row: unique vs duplicated pages (the paper's HBM-usage effect, §4) on the benchmark shapes."""
     import paper_2512_16822_amd as M
     got = {}
     for cfg in (2, 3, 4):

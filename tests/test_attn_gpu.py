@@ -212,7 +212,7 @@ def test_chunk_twice_in_one_request_uses_request_positions(mepic, oracle_attn):
     check(mepic, oracle_attn, case)
 
 
-# ------------------------------------------------------------------ the BASELINE configs at full size
+# ------------------------------------------------------------------ the benchmark configurations at full size
 def sample_rows(case, n, seed=0):
     rng = np.random.default_rng(seed)
     nq, Hq = case.n_q, case.st.Hq

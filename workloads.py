@@ -107,7 +107,7 @@ def prefill_structure(name: str, seed: int, *, B: int, Hq: int, Hkv: int, D: int
 
 
 def config(idx: int) -> Structure:
-    """The five workloads of the benchmark spec, by 1-based index (seed = 1000 + index)."""
+    """The five benchmark workloads, by 1-based index (seed = 1000 + index)."""
     seed = 1000 + idx
     if idx == 1:
         st = Structure("cfg1_tiny_decode_f32", "decode", 1, 8, 8, 64, 16, 1e4, "f32", "f32", seed)
