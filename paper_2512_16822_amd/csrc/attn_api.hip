@@ -92,7 +92,7 @@ Plan make_plan(const mepic_attn_params* p, bool prefill) {
     if (pl.n_splits < 1) pl.n_splits = 1;
     pl.blocks_per_split = n_blocks;
     // the per-position rotary table the call builds for itself: 32 entries of 16 bytes per position
-    pl.workspace_bytes = (size_t)prefill_mfma_table_positions(n_blocks * p->P) * 32 * sizeof(float4);
+    pl.workspace_bytes = (size_t)prefill_mfma_table_positions(n_blocks * p->P) * 16 * sizeof(uint4);
     return pl;
   }
 

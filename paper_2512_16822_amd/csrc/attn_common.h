@@ -73,7 +73,7 @@ hipError_t launch_combine(const AttnArgs& a, hipStream_t s);
 hipError_t launch_decode_mfma(const AttnArgs& a, hipStream_t s);  // bf16 or fp8 pages; includes its merge kernel
 hipError_t launch_prefill_mfma_bf16(const AttnArgs& a, hipStream_t s);  // n_splits = query tiles per request
 int prefill_mfma_rows_per_workgroup();
-int prefill_mfma_table_positions(int max_kv_len);                    // positions its rotary table covers (16 bytes x 32 each)
+int prefill_mfma_table_positions(int max_kv_len);                    // positions its rotary table covers (16 bytes x 16 each)
 void decode_mfma_plan(int B, int Hkv, int max_kv_len, bool fp8, int* max_splits, int* min_chunk);
 hipError_t launch_dot_rotate_selftest(const uint32_t* words, float* out, int n, hipStream_t s);
 hipError_t launch_mfma_rate_probe(int iters, float* sink, int n_workgroups, hipStream_t s);  // 512 threads each

@@ -61,23 +61,33 @@ typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;  // scal
 __device__ __forceinline__ int sload(const int32_t* p, size_t idx) { return ((const_i32_ptr)(uintptr_t)p)[idx]; }
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
-// Per-position rotary table: for position p and frequency pair (i0, i0 + 1), i0 = 8 pc + 2 j, one 16-byte entry
-// {cos(p f_i0), sin(p f_i0), cos(p f_i0+1), sin(p f_i0+1)} at entry index
-//   (((p / 64) * 8 + pc) * 4 + j) * 64 + p % 64,
-// so that the 64 lanes of a wave, which stage 64 consecutive positions for one (pc, j), read 1 KB in one piece.
-__device__ __forceinline__ size_t rope_entry(int p, int pc, int j) {
-  return ((((size_t)(p >> 6) * 8 + pc) * 4 + j) << 6) + (p & 63);
+// Per-position rotary table in half precision (11 significant bits: eight times finer than the bf16 rounding of the
+// rotated keys): for position p and the four frequencies i0 .. i0 + 3, i0 = 8 pc + 4 e, one 16-byte entry
+// {cos, sin}(p f_i0), {cos, sin}(p f_i0+1), ... at entry index
+//   (((p / 64) * 8 + pc) * 2 + e) * 64 + p % 64,
+// so that the 64 lanes of a wave, which stage 64 consecutive positions for one (pc, e), read 1 KB in one piece.
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+union HFrag {
+  uint4 u;
+  half8 h;
+};
+__device__ __forceinline__ size_t rope_entry(int p, int pc, int e) {
+  return ((((size_t)(p >> 6) * 8 + pc) * 2 + e) << 6) + (p & 63);
 }
 
 __global__ __launch_bounds__(256) void rope_table_kernel(const AttnArgs a, int n_pos) {
-  const int idx = blockIdx.x * 256 + threadIdx.x;   // (p / 64, pc, j, p % 64), the entry index itself
-  if (idx >= n_pos * 32) return;
-  const int p = ((idx >> 11) << 6) + (idx & 63), pc = (idx >> 8) & 7, j = (idx >> 6) & 3;
-  const int i0 = 8 * pc + 2 * j;
-  const float t0 = turns_frac((float)p, a.freq_hi[i0], a.freq_lo[i0]);
-  const float t1 = turns_frac((float)p, a.freq_hi[i0 + 1], a.freq_lo[i0 + 1]);
-  a.rope_table[idx] = make_float4(__builtin_amdgcn_cosf(t0), __builtin_amdgcn_sinf(t0), __builtin_amdgcn_cosf(t1),
-                                  __builtin_amdgcn_sinf(t1));
+  const int idx = blockIdx.x * 256 + threadIdx.x;   // (p / 64, pc, e, p % 64), the entry index itself
+  if (idx >= n_pos * 16) return;
+  const int p = ((idx >> 10) << 6) + (idx & 63), pc = (idx >> 7) & 7, e = (idx >> 6) & 1;
+  HFrag r;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int i = 8 * pc + 4 * e + j;
+    const float t = turns_frac((float)p, a.freq_hi[i], a.freq_lo[i]);
+    r.h[2 * j] = (_Float16)__builtin_amdgcn_cosf(t);
+    r.h[2 * j + 1] = (_Float16)__builtin_amdgcn_sinf(t);
+  }
+  reinterpret_cast<uint4*>(a.rope_table)[idx] = r.u;
 }
 
 // LDS tile layouts (per buffer):
@@ -171,38 +181,47 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_bf16_kernel(const At
   const int s_st = tid & 63, pc = wave;
   const uint4* kpages = reinterpret_cast<const uint4*>(a.k_pages);
   const uint4* vpages = reinterpret_cast<const uint4*>(a.v_pages);
-  const float4* table = a.rope_table + rope_entry(s_st, pc, 0);   // + 2048 entries per tile, + 64 per j
+  const uint4* table = reinterpret_cast<const uint4*>(a.rope_table) + rope_entry(s_st, pc, 0);   // + 1024 entries per tile, + 64 per e
   const size_t bt_row = (size_t)b * a.max_blocks;
   // V of a tile: wave w moves half w%2 (64 dims = 2 KB) of page-head w/2
   const int v_page_sel = wave >> 1, v_gran0 = (wave & 1) * 128 + lane;
 
-  Frag gk[2], gv[2];
-  float4 gt[4];
-  auto load_tile = [&](int t, int p0, int p1, int p2, int p3) __attribute__((always_inline)) {
+  // What a thread has in flight for one tile: two K granules, the table entries of its eight frequencies, two V
+  // granules. Two such sets: the loads of a tile are issued two tiles before they are staged.
+  struct Staged {
+    Frag gk[2], gv[2];
+    HFrag gt[2];
+  };
+  Staged set_a, set_b;
+  auto load_tile = [&](Staged& S, int t, int p0, int p1, int p2, int p3) __attribute__((always_inline)) {
     const int pg_k = (s_st < 32) ? (s_st < 16 ? p0 : p1) : (s_st < 48 ? p2 : p3);
     const size_t kb = ((size_t)pg_k * Hkv + hk) * (kD / 8 * kP) + (size_t)pc * kP + (s_st & 15);
-    gk[0].u = kpages[kb];
-    gk[1].u = kpages[kb + 8 * kP];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) gt[j] = table[(size_t)t * 2048 + j * 64];
+    S.gk[0].u = kpages[kb];
+    S.gk[1].u = kpages[kb + 8 * kP];
+    S.gt[0].u = table[(size_t)t * 1024];
+    S.gt[1].u = table[(size_t)t * 1024 + 64];
     const int pg_v = v_page_sel < 2 ? (v_page_sel == 0 ? p0 : p1) : (v_page_sel == 2 ? p2 : p3);  // wave-uniform
     const uint4* vsrc = vpages + ((size_t)pg_v * Hkv + hk) * (kD * 2) + v_gran0;
-    gv[0].u = vsrc[0];
-    gv[1].u = vsrc[64];
+    S.gv[0].u = vsrc[0];
+    S.gv[1].u = vsrc[64];
   };
   // rotate the staged K granules at position (tile start + s_st) and write them into LDS buffer `buf`; V goes there as
   // loaded, except that slots at or past kv_len, which may hold anything (NaN included: 0 x NaN would poison the
   // row), are zeroed
-  auto stage_tile = [&](int buf, int n0) __attribute__((always_inline)) {
+  auto stage_tile = [&](Staged& S, int buf, int n0) __attribute__((always_inline)) {
     Frag klo, khi;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-      const uint32_t lo2 = gk[0].w[w], hi2 = gk[1].w[w];
+      const uint32_t lo2 = S.gk[0].w[w], hi2 = S.gk[1].w[w];
       const float l0 = bf16_bits_to_f32(lo2), l1 = __uint_as_float(lo2 & 0xffff0000u);
       const float h0 = bf16_bits_to_f32(hi2), h1 = __uint_as_float(hi2 & 0xffff0000u);
-      const float4 r = gt[w];  // {cos, sin} of frequencies 8pc + 2w and 8pc + 2w + 1 at this slot's position
-      klo.w[w] = pack2(l0 * r.x - h0 * r.y, l1 * r.z - h1 * r.w);
-      khi.w[w] = pack2(h0 * r.x + l0 * r.y, h1 * r.z + l1 * r.w);
+      // {cos, sin} of frequencies 8pc + 2w and 8pc + 2w + 1 at this slot's position; the half-precision values feed
+      // mixed-precision multiply-adds directly (fma with a zero addend instead of a multiply keeps them unconverted)
+      const half8 r = S.gt[w >> 1].h;
+      const float c0 = (float)r[4 * (w & 1)], s0 = (float)r[4 * (w & 1) + 1];
+      const float c1 = (float)r[4 * (w & 1) + 2], s1 = (float)r[4 * (w & 1) + 3];
+      klo.w[w] = pack2(__builtin_fmaf(l0, c0, -__builtin_fmaf(h0, s0, 0.f)), __builtin_fmaf(l1, c1, -__builtin_fmaf(h1, s1, 0.f)));
+      khi.w[w] = pack2(__builtin_fmaf(h0, c0, __builtin_fmaf(l0, s0, 0.f)), __builtin_fmaf(h1, c1, __builtin_fmaf(l1, s1, 0.f)));
     }
     tiles[buf].k[pc * kTile + s_st] = klo.u;
     tiles[buf].k[(pc + 8) * kTile + s_st] = khi.u;
@@ -210,7 +229,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_bf16_kernel(const At
     for (int i = 0; i < 2; ++i) {
       const int gi = v_gran0 + 64 * i;              // granule of the page-head: dim gi / 2, slots 8 (gi & 1)..
       const int nbase = n0 + v_page_sel * kP + 8 * (gi & 1);
-      Frag x = gv[i];
+      Frag x = S.gv[i];
       if (nbase + 8 > L) {
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
@@ -230,9 +249,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_bf16_kernel(const At
   // Reference maximum of the row (log2 units). -inf until the row has seen a visible slot; rows that do not exist
   // (past the last query token: zero query, everything masked) start at 0 so that they never ask for attention.
   float m_run = row_ok ? -INFINITY : 0.f, l_part = 0.f;
-  floatx16 negm;  // minus the reference maximum in all sixteen elements: where the QK accumulators start
-#pragma unroll
-  for (int e = 0; e < 16; ++e) negm[e] = 0.f;
+  float negm = 0.f;   // minus the reference maximum: where the score accumulators start
 
   // Page ids of 16 tiles at a time: lane i of bt_cur holds the page of block 64 * bt_win + i (clamped to the
   // request's last block), bt_nxt the 64 after those; a tile reads its four ids with v_readlane. Vector loads on
@@ -266,32 +283,38 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_bf16_kernel(const At
   // page and the same of its second page.
   const int k_read = (l32 & 16) + ((l32 & 4) << 1) + ((l32 & 8) >> 1) + (l32 & 3);
 
+  // Operand j of a tile's 32 products: 0-7 K rows of slots 0-31, 8-15 K rows of slots 32-63, 16-23 V of pages 0, 1,
+  // 24-31 V of pages 2, 3.
+  constexpr int kRing = 4;
   auto tile_step = [&](int t, int buf) __attribute__((always_inline)) {
     const int n0 = t * kTile;
-
     const bool need_mask = n0 + kTile - 1 > min(pos_min, L - 1);  // some row cannot see the whole tile
-    // Operand ring: the LDS read of the operand that the product eight places later needs is issued right after
+    // Operand ring: the LDS read of the operand that the product kRing places later needs is issued right after
     // a product has consumed the ring entry, so that no product waits for LDS.
-    Frag ring[8];
+    Frag ring[kRing];
     const uint4* kt = tiles[buf].k + half * kTile + k_read;
     const uint4* vt = tiles[buf].v + l32 * 2 + (half ^ ((l32 >> 3) & 1));
+    auto operand = [&](int j) __attribute__((always_inline)) {
+      if (j < 16) return kt[2 * (j & 7) * kTile + 32 * (j >> 3)];
+      const int jj = j - 16;
+      return vt[((jj >> 2) * kD + 32 * (jj & 3)) * 2];
+    };
 #pragma unroll
-    for (int i = 0; i < 8; ++i) ring[i].u = kt[2 * i * kTile];
+    for (int i = 0; i < kRing; ++i) ring[i].u = operand(i);
     floatx16 sc2[2];
-    sc2[0] = negm;
+    {
+      float nm = negm;
+      asm volatile("" : "+v"(nm));   // a value of this tile: keeps sixteen copies of it from living across tiles
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      sc2[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i].v, bq[i].v, sc2[0], 0, 0, 0);
-      ring[i].u = kt[2 * i * kTile + 32];
+      for (int e = 0; e < 16; ++e) sc2[0][e] = sc2[1][e] = nm;
     }
-    sc2[1] = negm;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      sc2[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i].v, bq[i].v, sc2[1], 0, 0, 0);
-      ring[i].u = vt[((i >> 2) * kD + 32 * (i & 3)) * 2];          // pages 0, 1 of the tile
+    for (int i = 0; i < 16; ++i) {
+      sc2[i >> 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i % kRing].v, bq[i & 7].v, sc2[i >> 3], 0, 0, 0);
+      ring[i % kRing].u = operand(i + kRing);
     }
-    // pin the order: eight reads, then sixteen times (product, read of the operand eight products ahead)
-    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+    // pin the order: kRing reads, then sixteen times (product, read of the operand kRing products ahead)
+    __builtin_amdgcn_sched_group_barrier(0x100, kRing, 0);
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -330,8 +353,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_bf16_kernel(const At
           for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
-#pragma unroll
-          for (int e = 0; e < 16; ++e) negm[e] = -m_run;
+          negm = -m_run;
           if (sb == 0) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) sc2[1][e] -= delta;   // the second block's scores were shifted by the old reference
@@ -350,17 +372,20 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_bf16_kernel(const At
       for (int pp = 0; pp < 2; ++pp)
 #pragma unroll
         for (int w = 0; w < 4; ++w) pb[pp].w[w] = pack2(p[8 * pp + 2 * w], p[8 * pp + 2 * w + 1]);
+      int n_reads = 0;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[i].v, pb[i >> 2].v, o[i & 3], 0, 0, 0);
-        if (sb == 0) ring[i].u = vt[((2 + (i >> 2)) * kD + 32 * (i & 3)) * 2];   // pages 2, 3 of the tile
-      }
-      if (sb == 0) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        const int j = 16 + 8 * sb + i;
+        o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[j % kRing].v, pb[i >> 2].v, o[i & 3], 0, 0, 0);
+        if (j + kRing < 32) {
+          ring[j % kRing].u = operand(j + kRing);
+          ++n_reads;
         }
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (i < n_reads) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -368,32 +393,38 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_bf16_kernel(const At
   // Two groups of waves (one wave of each per SIMD) run the same sequence one segment apart, so that the matrix
   // segments of one fall on the vector segments of the other: group 0 stages the next tile BEFORE the tile's one
   // barrier, group 1 AFTER it. Three LDS buffers, so that staging tile t+1 never touches what tile t-1's products
-  // still read.
+  // still read. The global loads of tile t+3 are issued when tile t+1 has been staged out of their registers.
+  // Staging and loading are unconditional in the loop (past the last tile they repeat the last tile into a buffer
+  // nobody reads): the counts behind the compiler's waits for in-flight loads are then the same on every path.
   const int grp = wave >> 2;
-  if (n_tiles > 0) {
-    pages_of(0, np0, np1, np2, np3);
-    load_tile(0, np0, np1, np2, np3);
-    stage_tile(0, 0);
-    pages_of(1, np0, np1, np2, np3);
-    if (n_tiles > 1) load_tile(1, np0, np1, np2, np3);
-    lds_barrier();
-  }
+  const int t_last = n_tiles - 1;
   int bi = 0;
-  for (int t = 0; t < n_tiles; ++t) {
+  auto iteration = [&](Staged& S, int t) __attribute__((always_inline)) {   // S: the set that holds tile t + 1
     const int bn = bi + 1 == kNBuf ? 0 : bi + 1;
-    // page ids of tile t + 3: scalar loads, issued here so that the barrier's wait covers them (they share a counter
-    // with the LDS reads, and return out of order: one in flight would turn every LDS wait into a full drain)
     if (grp) lds_barrier();
-    if (t + 1 < n_tiles) {
-      stage_tile(bn, (t + 1) * kTile);
-      if (t + 2 < n_tiles) {
-        pages_of(t + 2, np0, np1, np2, np3);
-        load_tile(t + 2, np0, np1, np2, np3);
-      }
+    stage_tile(S, bn, min(t + 1, t_last) * kTile);
+    {
+      const int tn = min(t + 3, t_last);
+      pages_of(tn, np0, np1, np2, np3);
+      load_tile(S, tn, np0, np1, np2, np3);
     }
     if (!grp) lds_barrier();
-    tile_step(t, bi);
+    if (t < n_tiles) tile_step(t, bi);
     bi = bn;
+  };
+  if (n_tiles > 0) {
+    pages_of(0, np0, np1, np2, np3);
+    load_tile(set_a, 0, np0, np1, np2, np3);
+    pages_of(min(1, t_last), np0, np1, np2, np3);
+    load_tile(set_b, min(1, t_last), np0, np1, np2, np3);
+    stage_tile(set_a, 0, 0);
+    pages_of(min(2, t_last), np0, np1, np2, np3);
+    load_tile(set_a, min(2, t_last), np0, np1, np2, np3);
+    lds_barrier();
+    for (int t = 0; t < n_tiles; t += 2) {
+      iteration(set_b, t);
+      iteration(set_a, t + 1);
+    }
   }
 
   // ---- normalise and store: lane (row l32, half) holds dims 32db + 8blk + 4half + e of its row ----
@@ -450,7 +481,7 @@ hipError_t launch_mfma_rate_probe(int iters, float* sink, int n_workgroups, hipS
 // Rotary table, then the attention kernel. The optional timing events bracket the attention kernel alone.
 hipError_t launch_prefill_mfma_bf16(const AttnArgs& a, hipStream_t s) {
   const int n_pos = prefill_mfma_table_positions(a.blocks_per_split * a.P);
-  hipLaunchKernelGGL(rope_table_kernel, dim3((n_pos * 32 + 255) / 256), dim3(256), 0, s, a, n_pos);
+  hipLaunchKernelGGL(rope_table_kernel, dim3((n_pos * 16 + 255) / 256), dim3(256), 0, s, a, n_pos);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const unsigned grid = (unsigned)a.B * a.Hkv * a.n_splits;
