@@ -40,7 +40,7 @@ MEASURED_TRAFFIC = {
     ("cfg2", "decode_mfma_bf16"): int((583732.7 * 2.0 + 5221.9) * 1024),
     ("cfg4", "decode_mfma_bf16"): int((1115387.0 * 2.0 + 4236.3) * 1024),
     ("cfg5", "decode_mfma_fp8"): int((1124668.5 * 2.0 + 9258.6) * 1024),
-    ("cfg3", "prefill_mfma_bf16"): int((424860.0 * 2.0 + 34816.0) * 1024),
+    ("cfg3", "prefill_mfma_bf16"): int((374300.0 * 2.0 + 32770.0) * 1024),
     ("commit_bf16", "kv_commit"): int((131422.3 * 2.0 + 276860.1) * 1024),
     ("commit_fp8", "kv_commit"): int((131385.7 * 2.0 + 174081.0) * 1024),
     ("commit_decode", "kv_commit"): int((8283.7 * 2.0 + 147456.0) * 1024),
@@ -151,7 +151,7 @@ def oracle_sample(case, got, n_rows_total, cpu_seconds, prefill, flops, abytes):
                 max_abs_err_of_gpu_on_sample=err)
 
 
-def bench_attention(cfg: int, args, mfma_measured=None) -> dict:
+def bench_attention(cfg: int, args, mfma_measured=None, ref_mhz=None) -> dict:
     """One benchmark attention workload: every layout and call variant, its roofline record, the oracle beside it."""
     import numpy as np
     import torch
@@ -183,8 +183,16 @@ def bench_attention(cfg: int, args, mfma_measured=None) -> dict:
     call_ms, kern_ms = time_steps(dc, args.steps, args.warmup)
     kernel = M.last_kernel()
     shared_out = dc.out.float().cpu()
+    clock_ghz = None
     if prefill:
         layouts["shared"] = dict(call_ms=call_ms, kernel_ms=kern_ms, kernel=kernel, tflops=flops / (call_ms * 1e-3) / 1e12)
+        if kernel == "prefill_mfma_bf16" and ref_mhz:
+            # the kernel's own clock sample (workgroup 0; the last 16 bytes of the workspace size the library reports)
+            torch.cuda.synchronize()
+            off = M.attn_workspace_size(dc.params, True) - 16
+            clocks, ticks = [int(x) for x in dc.ws[off:off + 16].view(torch.int64).cpu()]
+            if 0 < ticks < 10 ** 9 and 0 < clocks < 10 ** 12:
+                clock_ghz = clocks / (ticks / (ref_mhz * 1e6)) / 1e9
         if not args.no_cold:
             layouts["shared"]["cold_call_ms"] = time_cold(dc)
     else:
@@ -239,6 +247,11 @@ def bench_attention(cfg: int, args, mfma_measured=None) -> dict:
         if mfma_measured:
             roofline["peak_measured"] = mfma_measured
             roofline["frac_of_measured"] = ach / mfma_measured
+        if clock_ghz:
+            # what the matrix cores could do at the clock the kernel actually ran at (the nominal peak is at 2.4 GHz)
+            roofline["clock_ghz"] = clock_ghz
+            roofline["peak_at_clock"] = MFMA_BF16_PEAK_TFLOPS * clock_ghz / 2.4
+            roofline["frac_at_clock"] = ach / roofline["peak_at_clock"]
         main = dict(value=flops / (call_ms * 1e-3) / 1e12, unit="TFLOP/s", ms=call_ms, layout="shared",
                     metric="fused-RoPE paged prefill attention throughput")
     else:
@@ -357,7 +370,7 @@ def bench_mfma_probe(args) -> dict:
     """The matrix-instruction-only kernel: what the chip sustains on v_mfma_f32_32x32x16_bf16 with every CU busy."""
     import torch
     import paper_2512_16822_amd as M
-    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda")
     iters = 20000
     for _ in range(2):
         M.probe_mfma_bf16(iters, sink)
@@ -371,7 +384,12 @@ def bench_mfma_probe(args) -> dict:
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1)
     tf = flop / (ms * 1e-3) / 1e12
+    # first wave of workgroup 0 of the last launch: core clocks and ticks of the constant-rate counter it ran for
+    clocks, ticks = float(sink[1]), float(sink[2])
+    ref_mhz = M.device_counter_khz() / 1e3
+    clock_ghz = clocks / (ticks / (ref_mhz * 1e6)) / 1e9 if ticks > 0 else None
     return dict(workload="mfma_only_bf16_32x32x16", tflops=tf, frac_of_nominal=tf / MFMA_BF16_PEAK_TFLOPS, ms=ms / 5,
+                clock_ghz=clock_ghz, ref_counter_mhz=ref_mhz,
                 main=dict(value=tf, unit="TFLOP/s", ms=ms / 5, layout="registers only", metric="matrix-instruction-only rate"),
                 roofline=dict(bound="mfma", achieved=tf, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s", frac=tf / MFMA_BF16_PEAK_TFLOPS,
                               traffic=None, kernel="mfma_rate", kernel_ms=ms / 5), cpu_baseline=None)
@@ -415,14 +433,15 @@ def main() -> int:
 
     t_all = time.perf_counter()
     records = {}
-    mfma = None
+    mfma = ref_mhz = None
     if "mfma_probe" in names or "cfg3" in names:
         records["mfma_probe"] = bench_mfma_probe(args)
         mfma = records["mfma_probe"]["tflops"]
+        ref_mhz = records["mfma_probe"]["ref_counter_mhz"]
     for n in names:
         t0 = time.perf_counter()
         if n.startswith("cfg"):
-            records[n] = bench_attention(int(n[3:]), args, mfma_measured=mfma)
+            records[n] = bench_attention(int(n[3:]), args, mfma_measured=mfma, ref_mhz=ref_mhz)
         elif n.startswith("commit_"):
             records[n] = bench_commit(n[len("commit_"):], args)
         if n in records:
@@ -439,7 +458,7 @@ def main() -> int:
                                                  "algorithmic_bytes", "unique_kv_bytes", "useful_flops", "new_tokens") if k in first}},
                 roofline=first["roofline"], cpu_baseline=first.get("cpu_baseline"),
                 layouts=first.get("layouts"), accounting=first.get("accounting"),
-                mfma_peak=dict(nominal_tflops=MFMA_BF16_PEAK_TFLOPS, measured_tflops=mfma) if mfma else None,
+                mfma_peak=dict(nominal_tflops=MFMA_BF16_PEAK_TFLOPS, measured_tflops=mfma, clock_ghz_measured=records["mfma_probe"]["clock_ghz"]) if mfma else None,
                 configs={k: v for k, v in records.items() if k != names[0]},
                 bench_wall_s=round(time.perf_counter() - t_all, 1))
     print(json.dumps(line))

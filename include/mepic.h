@@ -219,7 +219,11 @@ typedef struct {
  * flags, and WHETHER block_positions / block_valid_mask are NULL (they and the flags select the kernel, and the
  * kernels differ in what they need: split-K partials in decode, the per-position rotary table in the matrix-core
  * prefill). Query with the same flags and the same NULL-ness of those two pointers as the call will have;
- * a size queried otherwise can be too small, which the call reports as MEPIC_ERR_CAPACITY. */
+ * a size queried otherwise can be too small, which the call reports as MEPIC_ERR_CAPACITY.
+ * A measurement aid of the matrix-core prefill: the last 16 bytes of the size it reports receive two uint64, the
+ * core clocks and the ticks of the device's constant-rate counter (s_memrealtime) that workgroup 0 of the attention
+ * kernel ran for (written only if that workgroup has query tokens); their ratio tells the clock rate the kernel ran
+ * at, which the device's power management lowers under load. */
 int mepic_attn_workspace_size(const mepic_attn_params* params, int is_prefill, size_t* bytes_out);
 
 /* Decode: one query token per request attends to all of the request's valid slots (§3.3.3). */
@@ -254,9 +258,18 @@ const char* mepic_last_kernel(void);
  * accumulators per wave, two waves per SIMD, one workgroup per compute unit, `iters` rounds of four products) and
  * writes the floating-point operations it executes to *flop_out (host). The caller times it with events on the
  * stream: flop / time is the rate the device sustains on that instruction, to be read next to the nominal peak.
- * sink_device: device float[1] (never written in practice). Errors: MEPIC_ERR_INVALID, MEPIC_ERR_LAUNCH.
+ * sink_device: device float[4]; [0] is never written in practice, [1] and [2] receive the core clocks and the ticks
+ * of the constant-rate counter (s_memrealtime) that the first wave of workgroup 0 ran for, as floats:
+ * clocks / ticks x the counter's rate (mepic_device_counter_khz) is the clock rate under this load. (Of the two
+ * waves of a SIMD the older one is served first, so workgroup 0's first waves run for about half the launch.)
+ * Errors: MEPIC_ERR_INVALID, MEPIC_ERR_LAUNCH.
  */
 int mepic_probe_mfma_bf16(int32_t iters, float* sink_device, double* flop_out, void* hip_stream);
+
+/* Rate, in kHz, of the device's constant-rate counter (the one s_memrealtime reads; hipDeviceAttributeWallClockRate
+ * of the current device): what turns the tick counts above into seconds. Errors: MEPIC_ERR_INVALID (NULL),
+ * MEPIC_ERR_LAUNCH (the runtime's query failed). */
+int mepic_device_counter_khz(int32_t* khz_out);
 
 /*
  * Self-test of one building block, for the test suite (a guard against toolchain changes, not part of the method):

@@ -27,7 +27,7 @@ EXPORTS = ["mepic_strerror", "mepic_version", "mepic_pool_create", "mepic_pool_d
            "mepic_attn_decode", "mepic_attn_prefill", "mepic_last_kernel", "mepic_kv_commit",
            "mepic_decode_plan_capacity", "mepic_decode_plan_build", "mepic_attn_decode_batched_workspace_size",
            "mepic_attn_decode_batched", "mepic_attn_decode_noalloc", "mepic_selftest_dot_rotation",
-           "mepic_decode_plan_build_ahead", "mepic_probe_mfma_bf16"]
+           "mepic_decode_plan_build_ahead", "mepic_probe_mfma_bf16", "mepic_device_counter_khz"]
 
 
 class MepicError(RuntimeError):
@@ -283,12 +283,22 @@ def attn_decode_noalloc(params: AttnParams, stream=None) -> None:
 
 
 def probe_mfma_bf16(iters: int, sink, stream=None) -> float:
-    """mepic_probe_mfma_bf16: launches the matrix-instruction-only kernel; returns the flop it executes."""
+    """mepic_probe_mfma_bf16: launches the matrix-instruction-only kernel; returns the flop it executes.
+    sink: float32 tensor of 4 on the GPU; [1], [2] receive workgroup 0's core clocks and constant-rate ticks."""
     flop = ctypes.c_double()
     rc = load().mepic_probe_mfma_bf16(iters, _p(sink), ctypes.byref(flop), _stream_handle(stream))
     if rc != OK:
         raise MepicError(rc, "mepic_probe_mfma_bf16")
     return float(flop.value)
+
+
+def device_counter_khz() -> int:
+    """mepic_device_counter_khz: rate of the constant-rate counter behind the kernels' tick samples."""
+    khz = ctypes.c_int32()
+    rc = load().mepic_device_counter_khz(ctypes.byref(khz))
+    if rc != OK:
+        raise MepicError(rc, "mepic_device_counter_khz")
+    return int(khz.value)
 
 
 def selftest_dot_rotation(words, out, stream=None) -> None:

@@ -92,7 +92,7 @@ Plan make_plan(const mepic_attn_params* p, bool prefill) {
     if (pl.n_splits < 1) pl.n_splits = 1;
     pl.blocks_per_split = n_blocks;
     // the per-position rotary table the call builds for itself: 32 entries of 16 bytes per position
-    pl.workspace_bytes = (size_t)prefill_mfma_table_positions(n_blocks * p->P) * 16 * sizeof(uint4);
+    pl.workspace_bytes = (size_t)prefill_mfma_table_positions(n_blocks * p->P) * 16 * sizeof(uint4) + 16;  // table + clock sample
     return pl;
   }
 
@@ -297,6 +297,15 @@ int mepic_probe_mfma_bf16(int32_t iters, float* sink_device, double* flop_out, v
   *flop_out = (double)n_wg * 8.0 * (double)iters * 4.0 * (2.0 * 32 * 32 * 16);
   const hipError_t e = mepic::launch_mfma_rate_probe(iters, sink_device, n_wg, reinterpret_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? MEPIC_OK : MEPIC_ERR_LAUNCH;
+}
+
+int mepic_device_counter_khz(int32_t* khz_out) {
+  if (!khz_out) return MEPIC_ERR_INVALID;
+  int dev = 0, khz = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return MEPIC_ERR_LAUNCH;
+  if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz <= 0) return MEPIC_ERR_LAUNCH;
+  *khz_out = khz;
+  return MEPIC_OK;
 }
 
 int mepic_selftest_dot_rotation(const uint32_t* words_device, float* out_device, int32_t n, void* hip_stream) {

@@ -71,6 +71,7 @@ union HFrag {
   uint4 u;
   half8 h;
 };
+__host__ __device__ constexpr int prefill_table_positions(int max_kv_len) { return (max_kv_len + 63) / 64 * 64; }  // whole tiles
 __device__ __forceinline__ size_t rope_entry(int p, int pc, int e) {
   return ((((size_t)(p >> 6) * 8 + pc) * 2 + e) << 6) + (p & 63);
 }
@@ -116,6 +117,14 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_bf16_kernel(const At
   const int qt = (blockIdx.x / Hkv) % a.n_splits;  // n_splits carries the number of query tiles per request
   const int b = blockIdx.x / Hkv / a.n_splits;
 
+  // Workgroup 0 reports how long it ran in core clocks and in ticks of the constant-rate counter (16 bytes behind
+  // the rotary table): the ratio is the clock the kernel actually ran at, which power management sets well below
+  // the nominal one under this instruction mix.
+  unsigned long long clk0 = 0, rt0 = 0;
+  if (blockIdx.x == 0) {
+    clk0 = __builtin_readcyclecounter();
+    rt0 = __builtin_amdgcn_s_memrealtime();
+  }
   const int q_begin = sload(a.cu_q_lens, b), q_end = sload(a.cu_q_lens, b + 1);
   const int tok_per_wg = kRows / G;
   const int tok0 = q_begin + qt * tok_per_wg;
@@ -427,6 +436,12 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_bf16_kernel(const At
     }
   }
 
+  if (blockIdx.x == 0 && tid == 0) {
+    unsigned long long* sample = reinterpret_cast<unsigned long long*>(
+        reinterpret_cast<uint4*>(a.rope_table) + (size_t)prefill_table_positions(a.blocks_per_split * kP) * 16);
+    sample[0] = __builtin_readcyclecounter() - clk0;
+    sample[1] = __builtin_amdgcn_s_memrealtime() - rt0;
+  }
   // ---- normalise and store: lane (row l32, half) holds dims 32db + 8blk + 4half + e of its row ----
   {
     const uint32_t u = __float_as_uint(l_part);
@@ -453,6 +468,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_bf16_kernel(const At
 // wave, two waves per SIMD on every compute unit: the rate the chip sustains on this instruction (its clock sags
 // under that load), against which the prefill kernel's rate can be read next to the nominal peak.
 __global__ __launch_bounds__(kThreads, 1) void mfma_rate_kernel(int iters, float* sink) {
+  const unsigned long long clk0 = __builtin_readcyclecounter(), rt0 = __builtin_amdgcn_s_memrealtime();
   floatx16 acc[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j)
@@ -469,6 +485,10 @@ __global__ __launch_bounds__(kThreads, 1) void mfma_rate_kernel(int iters, float
 #pragma unroll
   for (int j = 0; j < 4; ++j) sum += acc[j][0] + acc[j][7] + acc[j][15];
   if (sum == 12345.678f) sink[0] = sum;  // never true in practice; keeps the products alive
+  if (blockIdx.x == 0 && threadIdx.x == 0) {   // core clocks and constant-rate ticks this workgroup ran for
+    sink[1] = (float)(__builtin_readcyclecounter() - clk0);
+    sink[2] = (float)(__builtin_amdgcn_s_memrealtime() - rt0);
+  }
 }
 
 }  // namespace
@@ -503,6 +523,6 @@ hipError_t launch_prefill_mfma_bf16(const AttnArgs& a, hipStream_t s) {
 int prefill_mfma_rows_per_workgroup() { return kRows; }
 
 // Positions the rotary table covers for contexts of up to max_kv_len slots: whole tiles of 64.
-int prefill_mfma_table_positions(int max_kv_len) { return (max_kv_len + kTile - 1) / kTile * kTile; }
+int prefill_mfma_table_positions(int max_kv_len) { return prefill_table_positions(max_kv_len); }
 
 }  // namespace mepic

