@@ -41,8 +41,10 @@ MEASURED_TRAFFIC = {
     ("cfg4", "decode_mfma_bf16"): int((1115387.0 * 2.0 + 4236.3) * 1024),
     ("cfg5", "decode_mfma_fp8"): int((1124668.5 * 2.0 + 9258.6) * 1024),
     ("cfg3", "prefill_mfma_bf16"): int((374300.0 * 2.0 + 32770.0) * 1024),
-    ("commit_bf16", "kv_commit"): int((131422.3 * 2.0 + 276860.1) * 1024),
-    ("commit_fp8", "kv_commit"): int((131385.7 * 2.0 + 174081.0) * 1024),
+    ("commit_bf16", "kv_commit"): int((131422.6 * 2.0 + 265693.8) * 1024),
+    ("commit_fp8", "kv_commit"): int((131432.1 * 2.0 + 131072.0) * 1024),
+    ("commit_bf16_unaligned", "kv_commit"): int((131422.3 * 2.0 + 276860.1) * 1024),
+    ("commit_fp8_unaligned", "kv_commit"): int((131385.7 * 2.0 + 174081.0) * 1024),
     ("commit_decode", "kv_commit"): int((8283.7 * 2.0 + 147456.0) * 1024),
 }
 ALL = ["cfg2", "cfg3", "cfg4", "cfg5", "commit_bf16", "commit_fp8", "commit_decode", "mfma_probe"]
@@ -292,18 +294,22 @@ def _timed(f) -> float:
 
 def bench_commit(kind: str, args) -> dict:
     """The commit step alone (scatter of new un-rotated K/V into their pages), Llama-3-8B KV shape (Hkv 8, D 128):
-    `bf16` / `fp8`: 64 requests x 1024 new tokens into bf16 pages of 16 slots / e4m3 pages of 32 slots (prompt commit);
+    `bf16` / `fp8`: 64 requests x 1024 new tokens into bf16 pages of 16 slots / e4m3 pages of 32 slots (prompt commit;
+    every run starts on a page boundary, as every segment of an aligned prompt does, §3.2.1);
+    `bf16_unaligned` / `fp8_unaligned` (only on request): the same with runs that start at slot 0, 8 or 16 of a page;
     `decode`: 4096 requests x one token into bf16 pages (what a decode step of a large batch commits per layer).
     HBM roofline on source bytes read + page bytes written."""
     import numpy as np
     import torch
     import paper_2512_16822_amd as M
     import workloads as W
+    unaligned = kind.endswith("_unaligned")
+    kind = kind.replace("_unaligned", "")
     fp8 = kind == "fp8"
     kv_dtype, P = ("f8e4m3", 32) if fp8 else ("bf16", 16)
     Hkv, D = 8, 128
     B, T = (4096, 1) if kind == "decode" else (64, 1024)
-    MB = 2 if kind == "decode" else T // P + 1
+    MB = 2 if kind == "decode" else T // P + 2
     dev = torch.device("cuda:0")
     rng = np.random.default_rng(10)
     pages = W.gen_pages(25, B * MB, Hkv, P, D, kv_dtype)
@@ -315,7 +321,8 @@ def bench_commit(kind: str, args) -> dict:
     k_dev, v_dev = pages.k.to(dev), pages.v.to(dev)
     ks = None if pages.k_scales is None else pages.k_scales.to(dev)
     vs = None if pages.v_scales is None else pages.v_scales.to(dev)
-    first = [int(rng.integers(P)) for _ in range(B)] if kind == "decode" else [(b % 3) * 8 for b in range(B)]
+    first = ([int(rng.integers(P)) for _ in range(B)] if kind == "decode" else
+             [(b % 3) * 8 for b in range(B)] if unaligned else [(b % 2) * P for b in range(B)])
     p = M.make_commit_params(k_new, v_new, k_dev, v_dev, i32(bt), i32(np.arange(B)), i32(first), i32(np.arange(B + 1) * T),
                              k_scales=ks, v_scales=vs)
     for _ in range(args.warmup):
@@ -340,12 +347,12 @@ def bench_commit(kind: str, args) -> dict:
     blocks_touched = B * (-(-(max(first) + T) // P))
     abytes = n_el * 2 + n_el * (1 if fp8 else 2) + blocks_touched * 4 + (blocks_touched * 8 if fp8 else 0) + (3 * B + 1) * 4
     ach = abytes / (kern_ms * 1e-3) / 1e9
-    rec = dict(workload=f"commit_{kind}_{B}x{T}_llama3_8b_{kv_dtype}", B=B, new_tokens=B * T, Hkv=Hkv, D=D, P=P,
+    rec = dict(workload=f"commit_{kind}{'_unaligned' if unaligned else ''}_{B}x{T}_llama3_8b_{kv_dtype}", B=B, new_tokens=B * T, Hkv=Hkv, D=D, P=P,
                dtype="bf16 -> e4m3" if fp8 else "bf16", algorithmic_bytes=abytes, call_ms=ms,
                main=dict(value=abytes / (ms * 1e-3) / 1e9, unit="GB/s", ms=ms, layout="private pages",
                          metric="KV commit throughput (source read + page write)"),
                roofline=dict(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS,
-                             traffic=MEASURED_TRAFFIC.get((f"commit_{kind}", "kv_commit")), kernel="kv_commit",
+                             traffic=MEASURED_TRAFFIC.get((f"commit_{kind}{'_unaligned' if unaligned else ''}", "kv_commit")), kernel="kv_commit",
                              kernel_ms=kern_ms, call_ms=ms, frac_call=abytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS))
     rec["cpu_baseline"] = None
     if not args.no_cpu_baseline:
@@ -413,7 +420,7 @@ def main() -> int:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         return 2
     names = [n for n in (args.only.split(",") if args.only else ([f"cfg{args.config}"] if args.config else ALL)) if n]
-    bad = [n for n in names if n not in ALL]
+    bad = [n for n in names if n not in ALL + ["commit_bf16_unaligned", "commit_fp8_unaligned"]]
     if bad:
         print(f"bench.py: unknown record(s) {bad}; known: {ALL}", file=sys.stderr)
         return 2
