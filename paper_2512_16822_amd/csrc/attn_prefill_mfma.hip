@@ -5,12 +5,13 @@
 // that share a KV head; 256/G tokens) of one (request, KV head) and walks the request's KV in tiles of
 // 64 slots (4 pages). What a tile costs is not matrix-pipe time but the waits of its two waves per SIMD (for
 // global loads, for LDS operands, for each other at the barrier), so the kernel is arranged around those:
-//   stage   every thread pulls two 16-byte granules of K and two of V from the pages (issued a whole tile before
-//           they are needed) and rotates K in registers at the slot's absolute position with cos/sin read from a
-//           per-position table (built once per call by rope_table_kernel: no trigonometry and no rotation state to
-//           advance in the loop), then writes both to LDS: K as bf16 in matrix-operand order, V as it lies in the
-//           page (16-byte pieces swapped pairwise so that operand reads hit every bank once). The rotated tile is
-//           shared by all 256 rows, so the rotation costs 1/256 per row.
+//   stage   every thread pulls two 16-byte granules of K and two of V from the pages (issued two whole tiles before
+//           they are needed, into two alternating register sets) and rotates K in registers at the slot's absolute
+//           position with cos/sin read from a per-position half-precision table (built once per call by
+//           rope_table_kernel: no trigonometry and no rotation state to advance in the loop), then writes both to
+//           LDS: K as bf16 in matrix-operand order, V as it lies in the page (16-byte pieces swapped pairwise so that
+//           operand reads hit every bank once). The rotated tile is shared by all 256 rows, so the rotation costs
+//           1/256 per row.
 //   QK      S^T[64 slots x 32 rows] per wave = Khat (LDS) x Qhat^T (registers), v_mfma_f32_32x32x16_bf16.
 //           Transposed so that a lane owns one query row: row sums are register-local. The accumulator starts
 //           at minus the row's reference maximum, so the scores come out of the products already shifted.
@@ -19,7 +20,7 @@
 //   softmax online; the reference maximum is a lower bound raised only when a probability would get huge (the
 //           test is on the row sum that is needed anyway), causal / length mask only on tiles that need it.
 //   PV      O^T[128 x 32 rows] += V^T (LDS) x P^T (the S^T registers, packed in place).
-// Matrix operands come from LDS through a ring of eight registers quadruples: the read for the product eight places
+// Matrix operands come from LDS through a ring of four register quadruples: the read for the product four places
 // ahead is issued right behind each product, so products do not wait for LDS. Three LDS tile buffers and ONE
 // barrier per tile; the waves of a SIMD belong to two groups that stage the next tile before, respectively after,
 // that barrier, which keeps them one segment apart. Page ids come 64 at a time through a vector load and
