@@ -37,9 +37,9 @@ PLAN_HORIZON = 32        # decode steps one plan built ahead serves
 # (counter readings in KiB, each scaled by what the same counter reads for a 1 GiB device copy: FETCH_SIZE x2.000,
 # WRITE_SIZE x1.000). Summaries with the commands are under profiles/.
 MEASURED_TRAFFIC = {
-    ("cfg2", "decode_mfma_bf16"): int((583732.7 * 2.0 + 5221.9) * 1024),
-    ("cfg4", "decode_mfma_bf16"): int((1115387.0 * 2.0 + 4236.3) * 1024),
-    ("cfg5", "decode_mfma_fp8"): int((1124668.5 * 2.0 + 9258.6) * 1024),
+    ("cfg2", "decode_mfma_bf16"): int((552111.8 * 2.0 + 5236.3) * 1024),
+    ("cfg4", "decode_mfma_bf16"): int((1050328.9 * 2.0 + 4266.7) * 1024),
+    ("cfg5", "decode_mfma_fp8"): int((1111731.1 * 2.0 + 9313.1) * 1024),
     ("cfg3", "prefill_mfma_bf16"): int((374300.0 * 2.0 + 32770.0) * 1024),
     ("commit_bf16", "kv_commit"): int((131422.6 * 2.0 + 265693.8) * 1024),
     ("commit_fp8", "kv_commit"): int((131432.1 * 2.0 + 131072.0) * 1024),

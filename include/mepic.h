@@ -176,7 +176,7 @@ enum {
   MEPIC_FLAG_KV_READ_ONCE = 4u      /* a hint, never a change of the result: (almost) no page is read by
                                        more than one request of this call (the pool's unique and logical
                                        page counts nearly agree). The matrix-core decode kernels then load
-                                       K/V with the non-temporal hint: faster when every byte comes from
+                                       V with the non-temporal hint: faster when every byte comes from
                                        HBM once anyway, slower when requests do share pages, whose reuse
                                        from the caches it defeats. Other kernels ignore it.            */
 };

@@ -204,7 +204,11 @@ constexpr float kPScaleFp8 = 4.f;     // probabilities (< 2^slack = 64) are mult
 // kBatched: the sequence a KV head's waves cut into chunks is the plan's list of runs (groups of up to 16/G
 // requests stepping through identical pages together) instead of the list of requests; a lane's matrix row then
 // belongs to request row / G of the run.
-// kReadOnce: the caller's hint that pages are not shared between the requests of the call (non-temporal loads).
+// kReadOnce: the caller's hint that pages are not shared between the requests of the call. V is then loaded
+// non-temporally (every V load instruction consumes whole 128-byte lines, so nothing is lost by not keeping them).
+// K keeps ordinary loads: the slot order that makes a lane's scores eight consecutive slots of a page lets one K load
+// instruction touch only half of each line it addresses and the next one the other half - with the hint a line was
+// sometimes gone in between and came from HBM twice (6-7 % more traffic, and slower than hinting V alone).
 template <bool kFp8, bool kBatched, bool kReadOnce = false>
 __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8, kBatched)) void decode_mfma_kernel(const AttnArgs a) {
   constexpr int kP = kFp8 ? 32 : 16;          // slots per page
@@ -321,14 +325,14 @@ __global__ __launch_bounds__(64 * kWaves, wg_per_cu(kFp8, kBatched)) void decode
 #pragma unroll
       for (int u = 0; u < 2; ++u)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) kf[u][j].u = load_page<kReadOnce>(&kpages[kb + (size_t)(4 * j) * kP + 4 * u]);
+        for (int j = 0; j < 2; ++j) kf[u][j].u = load_page<false>(&kpages[kb + (size_t)(4 * j) * kP + 4 * u]);
     } else {
       const int pk = (n16 < 8) ? p0 : p1;
       const size_t kb = ((size_t)pk * Hkv + hk) * (kD / 8 * kP) + (size_t)kg * kP + (slot_u0 & 15);
 #pragma unroll
       for (int u = 0; u < 2; ++u)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) kf[u][j].u = load_page<kReadOnce>(&kpages[kb + (size_t)(4 * j) * kP + 4 * u]);
+        for (int j = 0; j < 4; ++j) kf[u][j].u = load_page<false>(&kpages[kb + (size_t)(4 * j) * kP + 4 * u]);
     }
   };
   // V fragments, column tile nt = dim 16nt + n16: bf16: slots 8*(kg&1).. of page kg/2 (16 bytes);
