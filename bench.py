@@ -379,24 +379,44 @@ def bench_mfma_probe(args) -> dict:
     import paper_2512_16822_amd as M
     sink = torch.zeros(4, dtype=torch.float32, device="cuda")
     iters = 20000
-    for _ in range(2):
-        M.probe_mfma_bf16(iters, sink)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    flop = 0.0
-    for _ in range(5):
-        flop += M.probe_mfma_bf16(iters, sink)
-    e1.record()
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1)
-    tf = flop / (ms * 1e-3) / 1e12
-    # first wave of workgroup 0 of the last launch: core clocks and ticks of the constant-rate counter it ran for
-    clocks, ticks = float(sink[1]), float(sink[2])
     ref_mhz = M.device_counter_khz() / 1e3
-    clock_ghz = clocks / (ticks / (ref_mhz * 1e6)) / 1e9 if ticks > 0 else None
-    return dict(workload="mfma_only_bf16_32x32x16", tflops=tf, frac_of_nominal=tf / MFMA_BF16_PEAK_TFLOPS, ms=ms / 5,
-                clock_ghz=clock_ghz, ref_counter_mhz=ref_mhz,
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def rate(random_operands: bool):
+        for _ in range(2):
+            M.probe_mfma_bf16(iters, sink, random_operands=random_operands)
+        torch.cuda.synchronize()
+        e0.record()
+        flop = 0.0
+        for _ in range(5):
+            flop += M.probe_mfma_bf16(iters, sink, random_operands=random_operands)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        # first wave of workgroup 0 of the last launch: core clocks and ticks of the constant-rate counter it ran for
+        clocks, ticks = float(sink[1]), float(sink[2])
+        return flop / (ms * 1e-3) / 1e12, ms, (clocks / (ticks / (ref_mhz * 1e6)) / 1e9 if ticks > 0 else None)
+
+    tf_const, _, clock_const = rate(False)     # a few constant operand values: little toggling, the optimistic figure
+    tf, ms, clock_ghz = rate(True)             # pseudo-random operands: what the chip sustains on real data
+    # the prefill tile's instruction mix as synthetic in-order streams, in three arrangements (us per tile and CU)
+    buf = torch.zeros(1 << 14, dtype=torch.float32, device="cuda")
+    streams = {}
+    for structure, name in enumerate(("phases_all_waves_alike", "phases_two_groups", "uniform_stream")):
+        M.probe_tile_stream(structure, 500, buf)
+        torch.cuda.synchronize()
+        n_tiles = 4000
+        e0.record()
+        M.probe_tile_stream(structure, n_tiles, buf)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / n_tiles
+        c, t = float(buf[1]), float(buf[2])
+        streams[name] = dict(us_per_tile=us, clock_ghz=c / (t / (ref_mhz * 1e6)) / 1e9 if t > 0 else None,
+                             matrix_tflops=256 * 8 * 32 * 32768 / (us * 1e-6) / 1e12)   # 256 CUs x 8 waves x 32 products of 32 x 32 x 16
+    return dict(workload="mfma_only_bf16_32x32x16_random_operands", tflops=tf, frac_of_nominal=tf / MFMA_BF16_PEAK_TFLOPS, ms=ms / 5,
+                clock_ghz=clock_ghz, tflops_constant_operands=tf_const, clock_ghz_constant_operands=clock_const,
+                ref_counter_mhz=ref_mhz, tile_streams=streams,
                 main=dict(value=tf, unit="TFLOP/s", ms=ms / 5, layout="registers only", metric="matrix-instruction-only rate"),
                 roofline=dict(bound="mfma", achieved=tf, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s", frac=tf / MFMA_BF16_PEAK_TFLOPS,
                               traffic=None, kernel="mfma_rate", kernel_ms=ms / 5), cpu_baseline=None)
@@ -465,7 +485,9 @@ def main() -> int:
                                                  "algorithmic_bytes", "unique_kv_bytes", "useful_flops", "new_tokens") if k in first}},
                 roofline=first["roofline"], cpu_baseline=first.get("cpu_baseline"),
                 layouts=first.get("layouts"), accounting=first.get("accounting"),
-                mfma_peak=dict(nominal_tflops=MFMA_BF16_PEAK_TFLOPS, measured_tflops=mfma, clock_ghz_measured=records["mfma_probe"]["clock_ghz"]) if mfma else None,
+                mfma_peak=dict(nominal_tflops=MFMA_BF16_PEAK_TFLOPS, measured_tflops=mfma, clock_ghz_measured=records["mfma_probe"]["clock_ghz"],
+                               measured_tflops_constant_operands=records["mfma_probe"]["tflops_constant_operands"],
+                               clock_ghz_constant_operands=records["mfma_probe"]["clock_ghz_constant_operands"]) if mfma else None,
                 configs={k: v for k, v in records.items() if k != names[0]},
                 bench_wall_s=round(time.perf_counter() - t_all, 1))
     print(json.dumps(line))

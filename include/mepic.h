@@ -258,13 +258,30 @@ const char* mepic_last_kernel(void);
  * accumulators per wave, two waves per SIMD, one workgroup per compute unit, `iters` rounds of four products) and
  * writes the floating-point operations it executes to *flop_out (host). The caller times it with events on the
  * stream: flop / time is the rate the device sustains on that instruction, to be read next to the nominal peak.
+ * random_operands != 0: the operands are pseudo-random bf16 values instead of a few constants, so that the datapaths
+ * toggle as on real data; the device then settles at a lower clock (power), i.e. this is the fairer figure.
  * sink_device: device float[4]; [0] is never written in practice, [1] and [2] receive the core clocks and the ticks
  * of the constant-rate counter (s_memrealtime) that the first wave of workgroup 0 ran for, as floats:
  * clocks / ticks x the counter's rate (mepic_device_counter_khz) is the clock rate under this load. (Of the two
  * waves of a SIMD the older one is served first, so workgroup 0's first waves run for about half the launch.)
  * Errors: MEPIC_ERR_INVALID, MEPIC_ERR_LAUNCH.
  */
-int mepic_probe_mfma_bf16(int32_t iters, float* sink_device, double* flop_out, void* hip_stream);
+int mepic_probe_mfma_bf16(int32_t iters, int32_t random_operands, float* sink_device, double* flop_out, void* hip_stream);
+
+/*
+ * Second calibration kernel, for benchmarks (not part of the method): the instruction mix of one tile of the
+ * matrix-core prefill kernel as a synthetic in-order stream (per wave and tile: 32 matrix products with their A
+ * operand through an LDS ring, 112 vector instructions in the staging's mix, the softmax's 32 exponentials, 32 adds
+ * and 16 packs, four LDS writes, six cached global loads, one barrier; eight waves per workgroup, one workgroup per
+ * compute unit, `iters` tiles), in one of three arrangements: structure 0 = phases, all waves alike; 1 = phases, two
+ * groups of waves half a tile apart (the prefill kernel's arrangement); 2 = one uniform stream. The caller times the
+ * launch with events: time / iters is the time per tile this mix needs in that arrangement, to be read next to the
+ * prefill kernel's own time per tile.
+ * buf_device: device memory of buf_bytes >= 65536 that the kernel's loads read (any content); its floats [1], [2]
+ * receive the core clocks and constant-rate ticks of the first wave of workgroup 0, [0] is never written in practice.
+ * Errors: MEPIC_ERR_INVALID (structure not 0..2, iters < 0, NULL, buffer too small), MEPIC_ERR_LAUNCH.
+ */
+int mepic_probe_tile_stream(int32_t structure, int32_t iters, float* buf_device, size_t buf_bytes, void* hip_stream);
 
 /* Rate, in kHz, of the device's constant-rate counter (the one s_memrealtime reads; hipDeviceAttributeWallClockRate
  * of the current device): what turns the tick counts above into seconds. Errors: MEPIC_ERR_INVALID (NULL),

@@ -27,7 +27,8 @@ EXPORTS = ["mepic_strerror", "mepic_version", "mepic_pool_create", "mepic_pool_d
            "mepic_attn_decode", "mepic_attn_prefill", "mepic_last_kernel", "mepic_kv_commit",
            "mepic_decode_plan_capacity", "mepic_decode_plan_build", "mepic_attn_decode_batched_workspace_size",
            "mepic_attn_decode_batched", "mepic_attn_decode_noalloc", "mepic_selftest_dot_rotation",
-           "mepic_decode_plan_build_ahead", "mepic_probe_mfma_bf16", "mepic_device_counter_khz"]
+           "mepic_decode_plan_build_ahead", "mepic_probe_mfma_bf16", "mepic_device_counter_khz",
+           "mepic_probe_tile_stream"]
 
 
 class MepicError(RuntimeError):
@@ -115,8 +116,10 @@ def load() -> ctypes.CDLL:
     lib.mepic_attn_decode.argtypes = [ctypes.POINTER(AttnParams), ctypes.c_void_p]
     lib.mepic_attn_prefill.argtypes = [ctypes.POINTER(AttnParams), ctypes.c_void_p]
     lib.mepic_attn_decode_noalloc.argtypes = [ctypes.POINTER(AttnParams), ctypes.c_void_p]
-    lib.mepic_probe_mfma_bf16.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+    lib.mepic_probe_mfma_bf16.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
     lib.mepic_selftest_dot_rotation.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p]
+    lib.mepic_probe_tile_stream.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.mepic_device_counter_khz.argtypes = [ctypes.POINTER(ctypes.c_int32)]
     lib.mepic_kv_commit.argtypes = [ctypes.POINTER(CommitParams), ctypes.c_void_p]
     lib.mepic_decode_plan_capacity.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                                ctypes.POINTER(ctypes.c_size_t)]
@@ -282,14 +285,22 @@ def attn_decode_noalloc(params: AttnParams, stream=None) -> None:
         raise MepicError(rc, "mepic_attn_decode_noalloc")
 
 
-def probe_mfma_bf16(iters: int, sink, stream=None) -> float:
+def probe_mfma_bf16(iters: int, sink, stream=None, random_operands: bool = False) -> float:
     """mepic_probe_mfma_bf16: launches the matrix-instruction-only kernel; returns the flop it executes.
     sink: float32 tensor of 4 on the GPU; [1], [2] receive workgroup 0's core clocks and constant-rate ticks."""
     flop = ctypes.c_double()
-    rc = load().mepic_probe_mfma_bf16(iters, _p(sink), ctypes.byref(flop), _stream_handle(stream))
+    rc = load().mepic_probe_mfma_bf16(iters, int(random_operands), _p(sink), ctypes.byref(flop), _stream_handle(stream))
     if rc != OK:
         raise MepicError(rc, "mepic_probe_mfma_bf16")
     return float(flop.value)
+
+
+def probe_tile_stream(structure: int, iters: int, buf, stream=None) -> None:
+    """mepic_probe_tile_stream: buf = float32 tensor of >= 16384 elements on the GPU."""
+    rc = load().mepic_probe_tile_stream(structure, iters, _p(buf), ctypes.c_size_t(buf.numel() * buf.element_size()),
+                                        _stream_handle(stream))
+    if rc != OK:
+        raise MepicError(rc, "mepic_probe_tile_stream")
 
 
 def device_counter_khz() -> int:

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmepic.so")
-SOURCES = ["pool.cpp", "attn_api.hip", "attn_general.hip", "attn_decode_mfma.hip", "attn_prefill_mfma.hip", "kv_commit.hip", "decode_plan.cpp"]
+SOURCES = ["pool.cpp", "attn_api.hip", "attn_general.hip", "attn_decode_mfma.hip", "attn_prefill_mfma.hip", "kv_commit.hip", "decode_plan.cpp", "probes.hip"]
 # -packed-fp32-ops off: hipcc must not form v_pk_*_f32 from float code on these machines.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -290,12 +290,19 @@ int mepic_attn_prefill(const mepic_attn_params* params, void* hip_stream) {
 
 const char* mepic_last_kernel(void) { return mepic::g_last_kernel; }
 
-int mepic_probe_mfma_bf16(int32_t iters, float* sink_device, double* flop_out, void* hip_stream) {
+int mepic_probe_mfma_bf16(int32_t iters, int32_t random_operands, float* sink_device, double* flop_out, void* hip_stream) {
   if (iters < 0 || !sink_device || !flop_out) return MEPIC_ERR_INVALID;
   const int n_wg = mepic::device_compute_units();
   // per workgroup: 8 waves x iters x 4 products of 32 x 32 x 16 multiply-adds
   *flop_out = (double)n_wg * 8.0 * (double)iters * 4.0 * (2.0 * 32 * 32 * 16);
-  const hipError_t e = mepic::launch_mfma_rate_probe(iters, sink_device, n_wg, reinterpret_cast<hipStream_t>(hip_stream));
+  const hipError_t e = mepic::launch_mfma_rate_probe(iters, random_operands != 0, sink_device, n_wg, reinterpret_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? MEPIC_OK : MEPIC_ERR_LAUNCH;
+}
+
+int mepic_probe_tile_stream(int32_t structure, int32_t iters, float* buf_device, size_t buf_bytes, void* hip_stream) {
+  if (structure < 0 || structure > 2 || iters < 0 || !buf_device || buf_bytes < 65536) return MEPIC_ERR_INVALID;
+  const hipError_t e = mepic::launch_tile_stream_probe(structure, iters, buf_device, mepic::device_compute_units(),
+                                                        reinterpret_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? MEPIC_OK : MEPIC_ERR_LAUNCH;
 }
 

@@ -76,7 +76,8 @@ int prefill_mfma_rows_per_workgroup();
 int prefill_mfma_table_positions(int max_kv_len);                    // positions its rotary table covers (16 bytes x 16 each)
 void decode_mfma_plan(int B, int Hkv, int max_kv_len, bool fp8, int* max_splits, int* min_chunk);
 hipError_t launch_dot_rotate_selftest(const uint32_t* words, float* out, int n, hipStream_t s);
-hipError_t launch_mfma_rate_probe(int iters, float* sink, int n_workgroups, hipStream_t s);  // 512 threads each
+hipError_t launch_mfma_rate_probe(int iters, bool random_operands, float* sink, int n_workgroups, hipStream_t s);  // 512 threads each
+hipError_t launch_tile_stream_probe(int structure, int iters, float* buf, int n_workgroups, hipStream_t s);
 int device_compute_units();
 int decode_mfma_max_requests();                                       // B the plain walker's LDS has room for
 int decode_mfma_waves_per_head(int Hkv, bool fp8);                   // waves that share one KV head's steps

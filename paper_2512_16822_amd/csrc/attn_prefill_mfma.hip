@@ -465,39 +465,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_mfma_bf16_kernel(const At
   }
 }
 
-// Calibration of the matrix-core roofline: nothing but v_mfma_f32_32x32x16_bf16, four independent accumulators per
-// wave, two waves per SIMD on every compute unit: the rate the chip sustains on this instruction (its clock sags
-// under that load), against which the prefill kernel's rate can be read next to the nominal peak.
-__global__ __launch_bounds__(kThreads, 1) void mfma_rate_kernel(int iters, float* sink) {
-  const unsigned long long clk0 = __builtin_readcyclecounter(), rt0 = __builtin_amdgcn_s_memrealtime();
-  floatx16 acc[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
-  Frag x, y;
-  x.u = make_uint4(0x3f803f80u + threadIdx.x, 0x3f003f00u, 0x3e803e80u, 0x3f803f80u);
-  y.u = make_uint4(0x3c003c00u, 0x3b803b80u, 0x3c003c00u, 0x3b803b80u + blockIdx.x);
-  for (int it = 0; it < iters; ++it) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x.v, y.v, acc[j], 0, 0, 0);
-  }
-  float sum = 0.f;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) sum += acc[j][0] + acc[j][7] + acc[j][15];
-  if (sum == 12345.678f) sink[0] = sum;  // never true in practice; keeps the products alive
-  if (blockIdx.x == 0 && threadIdx.x == 0) {   // core clocks and constant-rate ticks this workgroup ran for
-    sink[1] = (float)(__builtin_readcyclecounter() - clk0);
-    sink[2] = (float)(__builtin_amdgcn_s_memrealtime() - rt0);
-  }
-}
-
 }  // namespace
-
-hipError_t launch_mfma_rate_probe(int iters, float* sink, int n_workgroups, hipStream_t s) {
-  hipLaunchKernelGGL(mfma_rate_kernel, dim3(n_workgroups), dim3(kThreads), 0, s, iters, sink);
-  return hipGetLastError();
-}
 
 // Rotary table, then the attention kernel. The optional timing events bracket the attention kernel alone.
 hipError_t launch_prefill_mfma_bf16(const AttnArgs& a, hipStream_t s) {

@@ -27,6 +27,35 @@ def test_every_declared_symbol_is_exported(mepic):
     assert mepic.last_kernel() == "" or isinstance(mepic.last_kernel(), str)
 
 
+def test_every_entry_point_with_arguments_declares_their_types(mepic):
+    """ctypes passes an undeclared Python int as a 32-bit C int: a device pointer handed to an entry point whose
+    argument types the binding forgot to declare would arrive truncated. Every export that takes arguments must
+    declare them, and the declaration must have as many entries as the header's parameter list."""
+    lib = mepic.load()
+    text = open(os.path.join(ROOT, "include", "mepic.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    for name in mepic.EXPORTS:
+        m = re.search(r"\b" + name + r"\s*\(([^;]*?)\)\s*;", text, flags=re.S)
+        assert m, name
+        params = m.group(1).strip()
+        n_params = 0 if params in ("", "void") else params.count(",") + 1
+        fn = getattr(lib, name)
+        if n_params == 0:
+            continue
+        assert fn.argtypes is not None, f"{name}: argument types not declared in the binding"
+        assert len(fn.argtypes) == n_params, f"{name}: {len(fn.argtypes)} declared, {n_params} in the header"
+
+
+def test_probe_argument_errors_are_rejected_before_any_launch(mepic):
+    lib = mepic.load()
+    assert lib.mepic_probe_tile_stream(3, 10, ctypes.c_void_p(0x1000), 65536, None) == mepic.ERR_INVALID
+    assert lib.mepic_probe_tile_stream(0, 10, None, 65536, None) == mepic.ERR_INVALID
+    assert lib.mepic_probe_tile_stream(0, 10, ctypes.c_void_p(0x1000), 1024, None) == mepic.ERR_INVALID
+    assert lib.mepic_probe_tile_stream(0, -1, ctypes.c_void_p(0x1000), 65536, None) == mepic.ERR_INVALID
+    assert lib.mepic_probe_mfma_bf16(-1, 0, ctypes.c_void_p(0x1000), ctypes.byref(ctypes.c_double()), None) == mepic.ERR_INVALID
+    assert lib.mepic_device_counter_khz(None) == mepic.ERR_INVALID
+
+
 def test_product_does_not_import_the_oracle():
     """The product path may not route through the oracle or any CPU fallback."""
     pkg = os.path.join(ROOT, "paper_2512_16822_amd")
