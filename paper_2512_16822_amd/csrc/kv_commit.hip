@@ -123,6 +123,8 @@ __global__ __launch_bounds__(kThreads) void kv_commit_kernel(const CommitArgs a)
   constexpr int DX = D / X;
   constexpr int kPitch = D * (int)sizeof(Dst) + 16;  // bytes per staged V row (keeps 16-byte alignment)
   constexpr int kGroups = kTile / 8;
+  // the V pass below enumerates the groups of eight tokens page by page: a tile must hold whole pages' worth of them
+  static_assert(kTile % P == 0 && kTile % 8 == 0 && kTile <= kThreads, "tile size does not fit the V pass");
   constexpr bool kNtStore = !std::is_same_v<Src, Dst>;  // see load_granule / store_granule
   __shared__ int s_page[kTile];                   // -1: nothing to write for this token
   __shared__ int s_slot[kTile];
