@@ -307,6 +307,18 @@ def test_prefill_matrix_core_group_sizes_and_ragged_kv(mepic, oracle_attn, G):
     check(mepic, oracle_attn, build_case(mepic, st), expect_kernel="prefill_mfma_bf16")
 
 
+@pytest.mark.parametrize("ctx", [17, 64, 65, 129, 193, 260])
+def test_prefill_contexts_of_one_to_five_tiles(mepic, oracle_attn, ctx):
+    """The tile loop's start-up and tail: loads run two tiles ahead and staging is unconditional past the last tile,
+    so contexts of one to five 64-slot tiles (odd and even counts, ragged ends) each take a different path."""
+    st = W.prefill_structure(f"prefill_ctx_{ctx}", 47, B=2, Hq=8, Hkv=2, D=128, P=16, theta=5e5, n_chunks=1,
+                             chunk_tokens=ctx, pool=2, q_tokens=1, max_gap_pages=0)
+    st.n_q = [9, 70]
+    for b, n in enumerate(st.n_q):
+        st.requests[b][-1] = (0, n + 3 * b, 0)
+    check(mepic, oracle_attn, build_case(mepic, st), expect_kernel="prefill_mfma_bf16")
+
+
 def test_prefill_queries_in_the_middle_and_far_positions(mepic, oracle_attn):
     """Query positions well inside the context (most of the KV is causally hidden) and positions around 40K."""
     st = W.prefill_structure("prefill_mid", 43, B=2, Hq=8, Hkv=2, D=128, P=16, theta=5e5, n_chunks=40,
